@@ -1,0 +1,271 @@
+/*
+ * CPU oracle of the KVSwap decode-step hot path -- TEST INFRASTRUCTURE ONLY.
+ * See kvswap_oracle.h for conventions and pins.  Plain C, fp64, no blocking,
+ * no fusion, no reordering: each function is the paper's statement of the
+ * step, written as loops.
+ */
+#include "kvswap_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- storage access ----------------------------------------------------- */
+
+static double load_elem(const void* base, int dtype, size_t i) {
+  if (dtype == ORC_F32) return (double)((const float*)base)[i];
+  uint32_t bits = (uint32_t)((const uint16_t*)base)[i] << 16; /* bf16 = top half of fp32 */
+  float f;
+  memcpy(&f, &bits, sizeof f);
+  return (double)f;
+}
+
+/* Nearest bf16 (8 significant bits, fp32 exponent range) to x, ties to even.
+ * The value is first snapped to the bf16 grid in fp64 (nearbyint rounds to
+ * nearest-even in the default rounding mode), which makes the following
+ * narrowing conversions exact. */
+uint16_t oracle_round_to_bf16(double x) {
+  if (x == 0.0 || isnan(x) || isinf(x)) {
+    float f = (float)x;
+    uint32_t b;
+    memcpy(&b, &f, sizeof b);
+    return (uint16_t)(b >> 16);
+  }
+  int e;
+  (void)frexp(x, &e);          /* |x| = m * 2^e, m in [0.5, 1)  => floor(log2|x|) = e-1 */
+  int ulp_exp = (e - 1) - 7;   /* spacing of bf16 numbers in this binade */
+  if (ulp_exp < -126 - 7) ulp_exp = -126 - 7; /* subnormal range: fixed spacing */
+  double y = ldexp(nearbyint(ldexp(x, -ulp_exp)), ulp_exp);
+  float f = (float)y;          /* exact, or +-inf on overflow */
+  uint32_t b;
+  memcpy(&b, &f, sizeof b);
+  return (uint16_t)(b >> 16);
+}
+
+static void store_meta(void* base, int dtype, size_t i, double x) {
+  if (dtype == ORC_F32) ((float*)base)[i] = (float)x; /* C conversion: nearest-even */
+  else ((uint16_t*)base)[i] = oracle_round_to_bf16(x);
+}
+
+static int params_ok(const orc_params* p) {
+  if (!p) return 0;
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->head_dim < 1 ||
+      p->rank < 1 || p->ctx_len < 1 || p->group_size < 1)
+    return 0;
+  if (p->n_q_heads % p->n_kv_heads) return 0;
+  if (p->ctx_len % p->group_size) return 0;
+  if (p->kv_dtype != ORC_F32 && p->kv_dtype != ORC_BF16) return 0;
+  if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16) return 0;
+  return 1;
+}
+
+/* ---- K_lr = K . A  (Sec. 4.2) -------------------------------------------- */
+
+int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
+                          void* K_lr, double* K_lr_exact) {
+  if (!params_ok(p) || !K || !A || !K_lr) return -1;
+  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
+  const long P = (long)p->batch * Hk;
+  long pi;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (pi = 0; pi < P; ++pi) {
+    const int k = (int)(pi % Hk);
+    const float* Ak = A + (size_t)k * d * r;
+    for (int n = 0; n < N; ++n) {
+      const size_t krow = ((size_t)pi * N + n) * d;
+      const size_t orow = ((size_t)pi * N + n) * r;
+      for (int j = 0; j < r; ++j) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i)
+          acc += load_elem(K, p->kv_dtype, krow + i) * (double)Ak[(size_t)i * r + j];
+        if (K_lr_exact) K_lr_exact[orow + j] = acc;
+        store_meta(K_lr, p->meta_dtype, orow + j, acc);
+      }
+    }
+  }
+  return 0;
+}
+
+/* ---- prediction + selection (Sec. 4.3) ----------------------------------- */
+
+typedef struct {
+  double score;
+  int32_t index;
+} scored_group;
+
+/* descending score; equal scores: ascending index */
+static int cmp_scored(const void* a, const void* b) {
+  const scored_group* x = (const scored_group*)a;
+  const scored_group* y = (const scored_group*)b;
+  if (x->score > y->score) return -1;
+  if (x->score < y->score) return 1;
+  return (x->index > y->index) - (x->index < y->index);
+}
+
+static int cmp_i32(const void* a, const void* b) {
+  const int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+  return (x > y) - (x < y);
+}
+
+int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
+                          const float* A, int32_t* idx, double* gs_out, double* s_out,
+                          double* boundary) {
+  if (!params_ok(p) || !q || !K_lr || !A || !idx) return -1;
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim, r = p->rank;
+  const int N = p->ctx_len, G = p->group_size, M = p->n_select;
+  const int NG = N / G, qpk = Hq / Hk;
+  if (M < 1 || M > NG) return -1;
+  const long P = (long)p->batch * Hk;
+  int failed = 0;
+  long pi;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (pi = 0; pi < P; ++pi) {
+    const int b = (int)(pi / Hk), k = (int)(pi % Hk);
+    const float* Ak = A + (size_t)k * d * r;
+    double* q_lr = (double*)malloc(sizeof(double) * (size_t)qpk * r);
+    double* s = (double*)malloc(sizeof(double) * (size_t)N);
+    scored_group* g = (scored_group*)malloc(sizeof(scored_group) * (size_t)NG);
+    if (!q_lr || !s || !g) {
+      failed = 1;
+      free(q_lr); free(s); free(g);
+      continue;
+    }
+    /* low-rank query vectors of the heads that share KV head k */
+    for (int hh = 0; hh < qpk; ++hh) {
+      const int h = k * qpk + hh;
+      const size_t qrow = ((size_t)b * Hq + h) * d;
+      for (int j = 0; j < r; ++j) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i)
+          acc += load_elem(q, p->kv_dtype, qrow + i) * (double)Ak[(size_t)i * r + j];
+        q_lr[(size_t)hh * r + j] = acc;
+      }
+    }
+    /* token importance: per-head low-rank logits, summed over the heads */
+    for (int n = 0; n < N; ++n) {
+      const size_t row = ((size_t)pi * N + n) * r;
+      double tot = 0.0;
+      for (int hh = 0; hh < qpk; ++hh) {
+        double acc = 0.0;
+        for (int j = 0; j < r; ++j)
+          acc += q_lr[(size_t)hh * r + j] * load_elem(K_lr, p->meta_dtype, row + j);
+        tot += acc;
+      }
+      s[n] = tot;
+      if (s_out) s_out[(size_t)pi * N + n] = tot;
+    }
+    /* group representative */
+    for (int j = 0; j < NG; ++j) {
+      double rep;
+      if (p->reduce == ORC_REDUCE_MEAN) {
+        rep = 0.0;
+        for (int t = 0; t < G; ++t) rep += s[(size_t)j * G + t];
+        rep /= (double)G;
+      } else {
+        rep = s[(size_t)j * G];
+        for (int t = 1; t < G; ++t)
+          if (s[(size_t)j * G + t] > rep) rep = s[(size_t)j * G + t];
+      }
+      g[j].score = rep;
+      g[j].index = j;
+      if (gs_out) gs_out[(size_t)pi * NG + j] = rep;
+    }
+    /* top-M groups, then ascending index order */
+    qsort(g, (size_t)NG, sizeof(scored_group), cmp_scored);
+    int32_t* out = idx + (size_t)pi * M;
+    for (int m = 0; m < M; ++m) out[m] = g[m].index;
+    qsort(out, (size_t)M, sizeof(int32_t), cmp_i32);
+    if (boundary) {
+      boundary[pi * 2 + 0] = g[M - 1].score;
+      boundary[pi * 2 + 1] = (M < NG) ? g[M].score : -INFINITY;
+    }
+    free(q_lr); free(s); free(g);
+  }
+  return failed ? -2 : 0;
+}
+
+/* ---- attention ----------------------------------------------------------- */
+
+/* softmax(scale * q.K[tok]) . V[tok] over the listed tokens of one (b, h) */
+static int attend_tokens(const orc_params* p, const void* q, const void* K, const void* V,
+                         int b, int h, const int32_t* tokens, long n_tok, double scale,
+                         double* out) {
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim, N = p->ctx_len;
+  const int k = h / (Hq / Hk);
+  const size_t qrow = ((size_t)b * Hq + h) * d;
+  const size_t kvbase = ((size_t)b * Hk + k) * (size_t)N * d;
+  double* z = (double*)malloc(sizeof(double) * (size_t)n_tok);
+  if (!z) return -2;
+  double zmax = -INFINITY;
+  for (long t = 0; t < n_tok; ++t) {
+    const size_t row = kvbase + (size_t)tokens[t] * d;
+    double acc = 0.0;
+    for (int i = 0; i < d; ++i)
+      acc += load_elem(q, p->kv_dtype, qrow + i) * load_elem(K, p->kv_dtype, row + i);
+    z[t] = scale * acc;
+    if (z[t] > zmax) zmax = z[t];
+  }
+  double denom = 0.0;
+  for (int i = 0; i < d; ++i) out[i] = 0.0;
+  for (long t = 0; t < n_tok; ++t) {
+    const double w = exp(z[t] - zmax);
+    const size_t row = kvbase + (size_t)tokens[t] * d;
+    denom += w;
+    for (int i = 0; i < d; ++i) out[i] += w * load_elem(V, p->kv_dtype, row + i);
+  }
+  for (int i = 0; i < d; ++i) out[i] /= denom;
+  free(z);
+  return 0;
+}
+
+static double resolve_scale(const orc_params* p) {
+  return p->softmax_scale != 0.0 ? p->softmax_scale : 1.0 / sqrt((double)p->head_dim);
+}
+
+int oracle_sparse_attn(const orc_params* p, const void* q, const void* K, const void* V,
+                       const int32_t* idx, double* out) {
+  if (!params_ok(p) || !q || !K || !V || !idx || !out) return -1;
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
+  const int G = p->group_size, M = p->n_select, NG = p->ctx_len / G;
+  if (M < 1 || M > NG) return -1;
+  for (long i = 0; i < (long)p->batch * Hk * M; ++i)
+    if (idx[i] < 0 || idx[i] >= NG) return -1;
+  const double scale = resolve_scale(p);
+  const long BH = (long)p->batch * Hq;
+  int failed = 0;
+  long bh;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (bh = 0; bh < BH; ++bh) {
+    const int b = (int)(bh / Hq), h = (int)(bh % Hq);
+    const int k = h / (Hq / Hk);
+    const int32_t* sel = idx + ((size_t)b * Hk + k) * M;
+    int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)M * G);
+    if (!tokens) { failed = 1; continue; }
+    for (int m = 0; m < M; ++m)
+      for (int t = 0; t < G; ++t) tokens[(size_t)m * G + t] = sel[m] * G + t;
+    if (attend_tokens(p, q, K, V, b, h, tokens, (long)M * G, scale, out + (size_t)bh * d))
+      failed = 1;
+    free(tokens);
+  }
+  return failed ? -2 : 0;
+}
+
+int oracle_dense_attn(const orc_params* p, const void* q, const void* K, const void* V,
+                      double* out) {
+  if (!params_ok(p) || !q || !K || !V || !out) return -1;
+  const int Hq = p->n_q_heads, d = p->head_dim, N = p->ctx_len;
+  const double scale = resolve_scale(p);
+  const long BH = (long)p->batch * Hq;
+  int failed = 0;
+  long bh;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (bh = 0; bh < BH; ++bh) {
+    const int b = (int)(bh / Hq), h = (int)(bh % Hq);
+    int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    if (!tokens) { failed = 1; continue; }
+    for (int n = 0; n < N; ++n) tokens[n] = n;
+    if (attend_tokens(p, q, K, V, b, h, tokens, N, scale, out + (size_t)bh * d)) failed = 1;
+    free(tokens);
+  }
+  return failed ? -2 : 0;
+}
