@@ -1,0 +1,132 @@
+/*
+ * kvswap_hip -- the decode-step hot path of KVSwap (arXiv 2511.11907) as
+ * hand-written HIP kernels for gfx950 (MI355X), behind a plain C ABI.
+ *
+ * One decode step of one layer, per (sequence b, KV head k) problem:
+ *   predict : s[n] = sum_{h: g(h)=k} (q[h] . A[k]) . K_lr[n]       (Sec. 4.3, Eq. 1)
+ *   group   : gs[j] = max (or mean) of s over the G tokens of group j
+ *   select  : idx = the M groups with the largest gs               (ReduceMax + TopK)
+ *   attend  : out[h] = softmax(scale * q[h] . K[sel]^T) . V[sel]    over the selected
+ *             groups' tokens only                                   (Sec. 4.4, KV cache manager)
+ * with the compact metadata K_lr = K . A built once per token (Sec. 4.2).
+ * The paper adopts one joint adapter for all KV heads; this library implements
+ * its per-head design (a): one adapter A[k] (d x r), one K_lr and one selection
+ * per KV head.  The full K/V cache lives in device memory (it stands in for the
+ * paper's disk tier plus preload buffer).
+ *
+ * Memory: every pointer below is a DEVICE pointer unless it says "host".  All
+ * tensors are contiguous and row-major, 16-byte aligned:
+ *   K, V          [B, H_kv, N, d]   kv_dtype      (a group = G consecutive rows,
+ *                                                  i.e. one contiguous G*d run)
+ *   q, out        [B, H_q, d]       kv_dtype
+ *   A             [H_kv, d, r]      fp32
+ *   K_lr          [B, H_kv, N, r]   meta_dtype
+ *   idx           [B, H_kv, M]      int32 group indices in [0, N/G), unique,
+ *                                   ascending as written by kvs_predict_select
+ *   group_scores  [B, H_kv, N/G]    fp32
+ * g(h) = h / (H_q / H_kv).
+ *
+ * Ownership: the caller owns every buffer.  The library allocates nothing,
+ * frees nothing, keeps no state between calls and never synchronises; all work
+ * is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ * stream).  Inputs are read-only.  `workspace` is caller-provided scratch of at
+ * least kvs_workspace_bytes() bytes; its contents are undefined on entry and on
+ * return, and two calls that share a workspace must be ordered on one stream.
+ *
+ * Errors: every function validates its arguments on the host before anything is
+ * launched and returns a kvs_status; nothing is thrown or aborted across the
+ * ABI.  Contents of idx are NOT validated on the device: out-of-range indices
+ * passed to kvs_sparse_decode_attn are a caller error.
+ *
+ * Supported shapes: d in {64, 128}; r in {16, 32, 64, 128} with r <= d;
+ * G in {1, 2, 4, 8, 16}; H_q / H_kv in {1, 2, 4, 8}; N % G == 0;
+ * 1 <= M <= N/G; N/G <= 32768; B * H_kv <= 65535; N * d < 2^31.
+ */
+#ifndef KVSWAP_HIP_H
+#define KVSWAP_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVS_OK = 0,
+  KVS_ERR_NULL = 1,        /* a required pointer is NULL                      */
+  KVS_ERR_SHAPE = 2,       /* inconsistent or non-positive sizes              */
+  KVS_ERR_DTYPE = 3,       /* unknown dtype / reduce code                     */
+  KVS_ERR_UNSUPPORTED = 4, /* consistent but outside the supported set        */
+  KVS_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small         */
+  KVS_ERR_DEVICE = 6,      /* a HIP launch reported an error                  */
+  KVS_ERR_ALIGN = 7        /* a tensor pointer is not 16-byte aligned         */
+} kvs_status;
+
+typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
+typedef enum { KVS_REDUCE_MAX = 0, KVS_REDUCE_MEAN = 1 } kvs_reduce;
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, rank; /* B, H_q, H_kv, d, r          */
+  int32_t ctx_len, group_size, n_select;                /* N, G, M                     */
+  int32_t kv_dtype;      /* kvs_dtype of K, V, q, out                                  */
+  int32_t meta_dtype;    /* kvs_dtype of K_lr                                          */
+  int32_t reduce;        /* kvs_reduce; MAX is the paper's ReduceMax                   */
+  float softmax_scale;   /* 0 => 1/sqrt(d)                                             */
+} kvs_params;
+
+/* Bytes of workspace that any of the calls below may need for these params
+ * (0 if the params are invalid). */
+size_t kvs_workspace_bytes(const kvs_params* p);
+
+/* Validate params without touching a device: KVS_OK or the error the other
+ * calls would return for them. */
+kvs_status kvs_check_params(const kvs_params* p);
+
+/* Sec. 4.2: K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32 accumulation, one rounding
+ * (nearest-even) to meta_dtype.  Run at prefill and whenever new groups are
+ * appended; not part of the per-step latency.  n_select is ignored. */
+kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A,
+                              void* K_lr, void* stream);
+
+/* Sec. 4.3 (Eq. 1, "Scoring and selection"): low-rank token scores summed over
+ * the query heads of each KV head, group representative (max or mean), and the
+ * indices of the M best groups per (b, kv head): ties go to the lower index,
+ * output ascending.  group_scores may be NULL; if given it receives gs. */
+kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_lr,
+                              const float* A, int32_t* idx, float* group_scores,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two halves of kvs_predict_select as separate calls (same arithmetic, same
+ * kernels): kvs_predict_scores writes group_scores [B,H_kv,N/G] (required here),
+ * kvs_select_topk reads them and writes idx.  Neither needs a workspace. */
+kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr,
+                              const float* A, float* group_scores, void* stream);
+kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
+                           void* stream);
+
+/* Sec. 4.4 (attention consumes only the selected KV groups): softmax attention
+ * of every query head over the G*M tokens named by idx of its KV head, gathered
+ * from the full K/V, fp32 online softmax, result rounded to kv_dtype. */
+kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K,
+                                  const void* V, const int32_t* idx, void* out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* One whole decode step of a layer: kvs_predict_select followed by
+ * kvs_sparse_decode_attn on the same stream with the fewest launches.  idx
+ * receives the selection (it is an output here); group_scores may be NULL. */
+kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
+                           const float* A, const void* K, const void* V, int32_t* idx,
+                           float* group_scores, void* out, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code (host pointer). */
+const char* kvs_status_str(kvs_status s);
+
+/* Library version string, e.g. "kvswap_hip 0.1 gfx950" (host pointer). */
+const char* kvs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSWAP_HIP_H */

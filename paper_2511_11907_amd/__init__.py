@@ -1,0 +1,12 @@
+"""kvswap_hip: the KVSwap decode-step hot path as HIP kernels for MI355X (gfx950).
+
+The package is a thin binding over the C-ABI library built from csrc/: argument
+marshalling only, every step of the path runs in the library's kernels.  There
+is no CPU fallback; a missing or unloadable library raises.
+"""
+from .binding import (  # noqa: F401
+    KVS_F32, KVS_BF16, KVS_REDUCE_MAX, KVS_REDUCE_MEAN,
+    KvsError, Params, load_library, library_path,
+    kvs_check_params, kvs_workspace_bytes, kvs_status_str, kvs_version,
+    kvs_build_metadata, kvs_predict_select, kvs_predict_scores, kvs_select_topk, kvs_sparse_decode_attn, kvs_decode_step,
+)

@@ -1,0 +1,261 @@
+"""ctypes binding of libkvswap_hip.so (declared in include/kvswap_hip.h).
+
+Functions carry the names of the C entry points and take torch tensors that
+already live on the GPU; this layer checks dtype / shape / contiguity, passes
+raw device pointers and the current HIP stream, and raises KvsError on any
+non-zero status.  torch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+from . import build as _build
+
+KVS_F32, KVS_BF16 = 0, 1
+KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
+
+EXPORTS = (
+    "kvs_workspace_bytes", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
+    "kvs_predict_scores", "kvs_select_topk",
+    "kvs_sparse_decode_attn", "kvs_decode_step", "kvs_status_str", "kvs_version",
+)
+
+
+class KvsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({kvs_status_str(status)})")
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
+        ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
+        ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32), ("reduce", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+    ]
+
+
+@dataclass
+class Params:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    rank: int
+    ctx_len: int
+    group_size: int
+    n_select: int
+    kv_dtype: int = KVS_BF16
+    meta_dtype: int = KVS_BF16
+    reduce: int = KVS_REDUCE_MAX
+    softmax_scale: float = 0.0
+
+    def _c(self) -> _CParams:
+        return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
+                        self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
+                        self.meta_dtype, self.reduce, self.softmax_scale)
+
+    @property
+    def n_groups(self) -> int:
+        return self.ctx_len // self.group_size
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; build it first only if no library is there.
+    Raises if it cannot be built or loaded -- there is no other code path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp, pp, sz = ctypes.c_void_p, ctypes.POINTER(_CParams), ctypes.c_size_t
+    lib.kvs_workspace_bytes.argtypes = [pp]
+    lib.kvs_workspace_bytes.restype = sz
+    lib.kvs_check_params.argtypes = [pp]
+    lib.kvs_check_params.restype = ctypes.c_int
+    lib.kvs_build_metadata.argtypes = [pp, vp, vp, vp, vp]
+    lib.kvs_build_metadata.restype = ctypes.c_int
+    lib.kvs_predict_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_predict_select.restype = ctypes.c_int
+    lib.kvs_predict_scores.argtypes = [pp, vp, vp, vp, vp, vp]
+    lib.kvs_predict_scores.restype = ctypes.c_int
+    lib.kvs_select_topk.argtypes = [pp, vp, vp, vp]
+    lib.kvs_select_topk.restype = ctypes.c_int
+    lib.kvs_sparse_decode_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_sparse_decode_attn.restype = ctypes.c_int
+    lib.kvs_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_decode_step.restype = ctypes.c_int
+    lib.kvs_status_str.argtypes = [ctypes.c_int]
+    lib.kvs_status_str.restype = ctypes.c_char_p
+    lib.kvs_version.argtypes = []
+    lib.kvs_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+# ---- helpers ------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_of(code: int):
+    torch = _torch()
+    return torch.float32 if code == KVS_F32 else torch.bfloat16
+
+
+def _dev(t, dtype, shape, name):
+    if t is None:
+        raise ValueError(f"{name} is required")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ws(workspace):
+    if workspace is None:
+        return ctypes.c_void_p(0), 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _stream(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise KvsError(status, what)
+
+
+# ---- entry points ---------------------------------------------------------------
+def kvs_status_str(status: int) -> str:
+    return load_library().kvs_status_str(int(status)).decode()
+
+
+def kvs_version() -> str:
+    return load_library().kvs_version().decode()
+
+
+def kvs_check_params(p: Params) -> int:
+    c = p._c()
+    return int(load_library().kvs_check_params(ctypes.byref(c)))
+
+
+def kvs_workspace_bytes(p: Params) -> int:
+    c = p._c()
+    return int(load_library().kvs_workspace_bytes(ctypes.byref(c)))
+
+
+def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:
+    torch = _torch()
+    kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    c = p._c()
+    st = load_library().kvs_build_metadata(
+        ctypes.byref(c),
+        _dev(K, kd, (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim), "K"),
+        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _stream(stream))
+    _check(st, "kvs_build_metadata")
+
+
+def kvs_predict_select(p: Params, q, K_lr, A, idx, group_scores, workspace, stream=None) -> None:
+    torch = _torch()
+    kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    c = p._c()
+    ws, nws = _ws(workspace)
+    gs = ctypes.c_void_p(0) if group_scores is None else _dev(
+        group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores")
+    st = load_library().kvs_predict_select(
+        ctypes.byref(c),
+        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        gs, ws, nws, _stream(stream))
+    _check(st, "kvs_predict_select")
+
+
+def kvs_predict_scores(p: Params, q, K_lr, A, group_scores, stream=None) -> None:
+    torch = _torch()
+    kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    c = p._c()
+    st = load_library().kvs_predict_scores(
+        ctypes.byref(c),
+        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+        _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
+        _stream(stream))
+    _check(st, "kvs_predict_scores")
+
+
+def kvs_select_topk(p: Params, group_scores, idx, stream=None) -> None:
+    torch = _torch()
+    c = p._c()
+    st = load_library().kvs_select_topk(
+        ctypes.byref(c),
+        _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
+        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _stream(stream))
+    _check(st, "kvs_select_topk")
+
+
+def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None) -> None:
+    torch = _torch()
+    kd = _dtype_of(p.kv_dtype)
+    c = p._c()
+    ws, nws = _ws(workspace)
+    kv_shape = (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim)
+    st = load_library().kvs_sparse_decode_attn(
+        ctypes.byref(c),
+        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+        _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
+        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
+        ws, nws, _stream(stream))
+    _check(st, "kvs_sparse_decode_attn")
+
+
+def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:
+    torch = _torch()
+    kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    c = p._c()
+    ws, nws = _ws(workspace)
+    kv_shape = (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim)
+    gs = ctypes.c_void_p(0) if group_scores is None else _dev(
+        group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores")
+    st = load_library().kvs_decode_step(
+        ctypes.byref(c),
+        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+        _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
+        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        gs,
+        _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
+        ws, nws, _stream(stream))
+    _check(st, "kvs_decode_step")

@@ -1,0 +1,209 @@
+// C ABI of kvswap_hip: argument validation, launch planning and the entry points
+// declared in include/kvswap_hip.h.  Everything here runs on the host; all checks
+// are done before the first launch.
+#include <math.h>
+
+#include "kernels.h"
+
+namespace kvs {
+
+namespace {
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+}  // namespace
+
+Plan make_plan(const kvs_params& p) {
+  Plan pl{};
+  pl.problems = p.batch * p.n_kv_heads;
+  pl.n_groups = p.ctx_len / p.group_size;
+  pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
+
+  // predict: enough workgroups to cover the chip several times, each streaming at
+  // least one full step of 4 waves x 8 loads
+  const int meta_epl = p.meta_dtype == KVS_BF16 ? 8 : 4;
+  pl.meta_lanes_per_row = p.rank / meta_epl;
+  pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;
+  pl.predict_units = ceil_div(p.ctx_len, pl.meta_rows_per_unit);
+  {
+    const int want = ceil_div(2048, pl.problems);
+    const int most = ceil_div(pl.predict_units, kPredictUnitsPerWgStep);
+    const int chunks = want < 1 ? 1 : (want > most ? most : want);
+    pl.predict_units_per_wg = round_up(ceil_div(pl.predict_units, chunks), kPredictUnitsPerWgStep);
+    pl.predict_chunks = ceil_div(pl.predict_units, pl.predict_units_per_wg);
+  }
+
+  // attention: split the selected tokens of a problem over workgroups
+  const int kv_epl = p.kv_dtype == KVS_BF16 ? 8 : 4;
+  pl.kv_lanes_per_tok = p.head_dim / kv_epl;
+  pl.kv_toks_per_unit = 64 / pl.kv_lanes_per_tok;
+  pl.attn_units = ceil_div(p.n_select * p.group_size, pl.kv_toks_per_unit);
+  {
+    const int want = ceil_div(1024, pl.problems);
+    const int most = ceil_div(pl.attn_units, kAttnUnitsPerWgStep);
+    const int splits = want < 1 ? 1 : (want > most ? most : want);
+    pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWgStep);
+    pl.attn_splits = ceil_div(pl.attn_units, pl.attn_units_per_split);
+  }
+
+  size_t off = 0;
+  pl.off_gs = off;
+  off += align256((size_t)pl.problems * pl.n_groups * sizeof(float));
+  pl.off_part_ml = off;
+  off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * 2 * sizeof(float));
+  pl.off_part_o = off;
+  off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * p.head_dim * sizeof(float));
+  pl.total_bytes = off;
+  return pl;
+}
+
+namespace {
+
+kvs_status check_params(const kvs_params* p, bool need_select) {
+  if (!p) return KVS_ERR_NULL;
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->head_dim < 1 || p->rank < 1 ||
+      p->ctx_len < 1 || p->group_size < 1)
+    return KVS_ERR_SHAPE;
+  if ((p->kv_dtype != KVS_F32 && p->kv_dtype != KVS_BF16) ||
+      (p->meta_dtype != KVS_F32 && p->meta_dtype != KVS_BF16) ||
+      (p->reduce != KVS_REDUCE_MAX && p->reduce != KVS_REDUCE_MEAN))
+    return KVS_ERR_DTYPE;
+  if (p->n_q_heads % p->n_kv_heads) return KVS_ERR_SHAPE;
+  if (p->ctx_len % p->group_size) return KVS_ERR_SHAPE;
+  if (p->rank > p->head_dim) return KVS_ERR_SHAPE;
+  if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return KVS_ERR_SHAPE;
+  const int ng = p->ctx_len / p->group_size;
+  if (need_select && (p->n_select < 1 || p->n_select > ng)) return KVS_ERR_SHAPE;
+  // supported set
+  if (p->head_dim != 64 && p->head_dim != 128) return KVS_ERR_UNSUPPORTED;
+  if (p->rank != 16 && p->rank != 32 && p->rank != 64 && p->rank != 128) return KVS_ERR_UNSUPPORTED;
+  if (!is_pow2(p->group_size) || p->group_size > 16) return KVS_ERR_UNSUPPORTED;
+  const int qpk = p->n_q_heads / p->n_kv_heads;
+  if (!is_pow2(qpk) || qpk > 8) return KVS_ERR_UNSUPPORTED;
+  if (ng > 32768) return KVS_ERR_UNSUPPORTED;
+  // index arithmetic inside the kernels is 32-bit per problem and 64-bit across problems
+  if ((long long)p->ctx_len * p->head_dim >= (1ll << 31)) return KVS_ERR_UNSUPPORTED;
+  if ((long long)p->batch * p->n_kv_heads > 65535) return KVS_ERR_UNSUPPORTED;  // gridDim.y
+  return KVS_OK;
+}
+
+inline bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15u) != 0; }
+
+kvs_status check_workspace(const Plan& pl, const void* ws, size_t bytes) {
+  if (!ws || misaligned(ws) || bytes < pl.total_bytes) return KVS_ERR_WORKSPACE;
+  return KVS_OK;
+}
+
+inline kvs_status dev(hipError_t e) { return e == hipSuccess ? KVS_OK : KVS_ERR_DEVICE; }
+
+}  // namespace
+}  // namespace kvs
+
+using namespace kvs;
+
+extern "C" {
+
+kvs_status kvs_check_params(const kvs_params* p) { return check_params(p, true); }
+
+size_t kvs_workspace_bytes(const kvs_params* p) {
+  if (check_params(p, true) != KVS_OK) return 0;
+  return make_plan(*p).total_bytes;
+}
+
+kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A, void* K_lr,
+                              void* stream) {
+  if (!p || !K || !A || !K_lr) return KVS_ERR_NULL;
+  kvs_params q = *p;
+  q.n_select = 1;  // not used by this call
+  const kvs_status s = check_params(&q, false);
+  if (s != KVS_OK) return s;
+  if (misaligned(K) || misaligned(A) || misaligned(K_lr)) return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(q);
+  return dev(launch_build_metadata(q, pl, K, A, K_lr, (hipStream_t)stream));
+}
+
+kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_lr, const float* A,
+                              int32_t* idx, float* group_scores, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!p || !q || !K_lr || !A || !idx) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(q) || misaligned(K_lr) || misaligned(A) || misaligned(idx) ||
+      (group_scores && misaligned(group_scores)))
+    return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+  float* gs = group_scores ? group_scores : (float*)((char*)workspace + pl.off_gs);
+  hipStream_t st = (hipStream_t)stream;
+  if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, st))) != KVS_OK) return s;
+  return dev(launch_topk(*p, pl, gs, idx, st));
+}
+
+kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr, const float* A,
+                              float* group_scores, void* stream) {
+  if (!p || !q || !K_lr || !A || !group_scores) return KVS_ERR_NULL;
+  const kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(q) || misaligned(K_lr) || misaligned(A) || misaligned(group_scores))
+    return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, (hipStream_t)stream));
+}
+
+kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
+                           void* stream) {
+  if (!p || !group_scores || !idx) return KVS_ERR_NULL;
+  const kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(group_scores) || misaligned(idx)) return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  return dev(launch_topk(*p, pl, group_scores, idx, (hipStream_t)stream));
+}
+
+kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, void* out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (!p || !q || !K || !V || !idx || !out) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(out))
+    return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+  float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
+  float* part_o = (float*)((char*)workspace + pl.off_part_o);
+  hipStream_t st = (hipStream_t)stream;
+  if ((s = dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, st))) != KVS_OK) return s;
+  return dev(launch_combine(*p, pl, part_ml, part_o, out, st));
+}
+
+kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr, const float* A,
+                           const void* K, const void* V, int32_t* idx, float* group_scores,
+                           void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!p || !q || !K_lr || !A || !K || !V || !idx || !out) return KVS_ERR_NULL;
+  kvs_status s = kvs_predict_select(p, q, K_lr, A, idx, group_scores, workspace, workspace_bytes,
+                                    stream);
+  if (s != KVS_OK) return s;
+  return kvs_sparse_decode_attn(p, q, K, V, idx, out, workspace, workspace_bytes, stream);
+}
+
+const char* kvs_status_str(kvs_status s) {
+  switch (s) {
+    case KVS_OK: return "ok";
+    case KVS_ERR_NULL: return "a required pointer is NULL";
+    case KVS_ERR_SHAPE: return "inconsistent sizes";
+    case KVS_ERR_DTYPE: return "unknown dtype or reduce code";
+    case KVS_ERR_UNSUPPORTED: return "shape outside the supported set";
+    case KVS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KVS_ERR_DEVICE: return "HIP launch failed";
+    case KVS_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+  }
+  return "unknown status";
+}
+
+const char* kvs_version(void) { return "kvswap_hip 0.1 gfx950"; }
+
+}  // extern "C"

@@ -1,0 +1,273 @@
+// Attention over the selected KV groups only (Sec. 4.4: the attention kernel consumes
+// the groups the predictor chose; here they are gathered straight from the full
+// K/V in HBM, which stands in for the paper's preload buffer).
+//
+// Split-K flash-decode.  A (sequence, KV head) problem owns M groups = M*G tokens;
+// the token list is cut into "units" of one wave-wide 16-byte-per-lane load
+// (64/LPT tokens, LPT lanes per token), units are dealt to `attn_splits`
+// workgroups, and inside a workgroup to its four waves.  All H_q/H_kv query heads
+// that share the KV head are processed together so K and V are read once (GQA
+// head packing).  A lane keeps, for its 16-byte column of the head dimension, an
+// independent online-softmax state (running max, running sum, weighted V sum) per
+// head for the token slot it serves; slots, waves and finally splits are merged
+// with the usual log-sum-exp rescaling.  A group is G consecutive rows, i.e. one
+// contiguous run of G*d elements, so with G*LPT = 64 a unit is exactly one group
+// and every wave-wide load is a fully used 1 KiB burst.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace kvs {
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kAttnUnroll = 4;       // units (K load + V load each) in flight per wave
+constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <typename E, int D, int QPK>
+__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
+    const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
+    const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
+    float* __restrict__ part_ml, float* __restrict__ part_o, int n_kv_heads, int N, int M,
+    int log2G, int units, int units_per_split, int n_splits, float scale_log2e) {
+  constexpr int EPL = E::kPerLane;
+  constexpr int LPT = D / EPL;       // lanes per token row
+  constexpr int TPU = kWave / LPT;   // tokens per unit
+  static_assert(LPT == 8 || LPT == 16 || LPT == 32, "row must span 8, 16 or 32 lanes");
+
+  // per-wave partial states, merged by the whole workgroup at the end
+  __shared__ float s_m[kAttnWaves][QPK];
+  __shared__ float s_l[kAttnWaves][QPK];
+  __shared__ float s_w[kAttnWaves][QPK];
+  __shared__ float s_o[kAttnWaves][QPK][D];
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int split = blockIdx.x, p = blockIdx.y;
+  const int b = p / n_kv_heads, k = p % n_kv_heads;
+  const int n_q_heads = n_kv_heads * QPK;
+  const int c = lane % LPT;   // 16-byte column of the row
+  const int ts = lane / LPT;  // token slot within the unit
+  const int G = 1 << log2G;
+  const int n_tok = M << log2G;
+
+  // queries of the QPK heads of this KV head, pre-multiplied by scale*log2(e)
+  float qr[QPK][EPL];
+#pragma unroll
+  for (int h = 0; h < QPK; ++h) {
+    const size_t off = ((size_t)b * n_q_heads + (size_t)k * QPK + h) * D + (size_t)c * EPL;
+    const uint4 v = *reinterpret_cast<const uint4*>(q + off);
+    unpack16<E>(v, qr[h]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qr[h][e] *= scale_log2e;
+  }
+
+  float m[QPK], l[QPK], o[QPK][EPL];
+#pragma unroll
+  for (int h = 0; h < QPK; ++h) {
+    m[h] = kNegBig;
+    l[h] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[h][e] = 0.f;
+  }
+
+  const typename E::storage* Kp = K + (size_t)p * N * D;
+  const typename E::storage* Vp = V + (size_t)p * N * D;
+  const int32_t* sel = idx + (size_t)p * M;
+  const int u0 = split * units_per_split;
+  const int u1 = min(units, u0 + units_per_split);
+
+  for (int ub = u0 + wave * kAttnUnroll; ub < u1; ub += kAttnWaves * kAttnUnroll) {
+    bool ok[kAttnUnroll];
+    size_t off[kAttnUnroll];
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      const int tok = (ub + u) * TPU + ts;  // position in the selected-token list
+      ok[u] = (ub + u < u1) && (tok < n_tok);
+      const int grp = ok[u] ? sel[tok >> log2G] : 0;
+      const int row = (grp << log2G) + (tok & (G - 1));
+      off[u] = (size_t)(ok[u] ? row : 0) * D + (size_t)c * EPL;
+    }
+    uint4 kv[kAttnUnroll], vv[kAttnUnroll];
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) kv[u] = *reinterpret_cast<const uint4*>(Kp + off[u]);
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) vv[u] = *reinterpret_cast<const uint4*>(Vp + off[u]);
+
+    // logits (already in log2 units) of this slot's token against each head
+    float z[kAttnUnroll][QPK];
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      float kf[EPL];
+      unpack16<E>(kv[u], kf);
+#pragma unroll
+      for (int h = 0; h < QPK; ++h) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc = fmaf(qr[h][e], kf[e], acc);
+        z[u][h] = allreduce_lanes<OpSum, 1, LPT>(acc);
+      }
+    }
+    // online softmax update, one rescale per batch
+    float pw[kAttnUnroll][QPK];
+#pragma unroll
+    for (int h = 0; h < QPK; ++h) {
+      float mn = m[h];
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) mn = ok[u] ? fmaxf(mn, z[u][h]) : mn;
+      const float alpha = __builtin_amdgcn_exp2f(m[h] - mn);
+      m[h] = mn;
+      float ls = l[h] * alpha;
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) {
+        pw[u][h] = ok[u] ? __builtin_amdgcn_exp2f(z[u][h] - mn) : 0.f;
+        ls += pw[u][h];
+      }
+      l[h] = ls;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[h][e] *= alpha;
+    }
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      float vf[EPL];
+      unpack16<E>(vv[u], vf);
+#pragma unroll
+      for (int h = 0; h < QPK; ++h)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pw[u][h], vf[e], o[h][e]);
+    }
+  }
+
+  // ---- merge the token slots of the wave (lanes with equal column c) ------------
+#pragma unroll
+  for (int h = 0; h < QPK; ++h) {
+    const float mw = allreduce_lanes<OpMax, LPT, kWave>(m[h]);
+    const float w = __builtin_amdgcn_exp2f(m[h] - mw);
+    m[h] = mw;
+    l[h] = allreduce_lanes<OpSum, LPT, kWave>(l[h] * w);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[h][e] = allreduce_lanes<OpSum, LPT, kWave>(o[h][e] * w);
+  }
+  // ---- merge the waves of the workgroup ------------------------------------------
+  if (ts == 0) {
+#pragma unroll
+    for (int h = 0; h < QPK; ++h) {
+      if (c == 0) {
+        s_m[wave][h] = m[h];
+        s_l[wave][h] = l[h];
+      }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_o[wave][h][c * EPL + e] = o[h][e];
+    }
+  }
+  __syncthreads();
+  // per head: global max, weights, sum of l
+  float* ml = part_ml + ((size_t)p * n_splits + split) * QPK * 2;
+  if (tid < QPK) {
+    float mt = kNegBig;
+    for (int s = 0; s < kAttnWaves; ++s) mt = fmaxf(mt, s_m[s][tid]);
+    float lt = 0.f;
+    for (int s = 0; s < kAttnWaves; ++s) {
+      const float w = __builtin_amdgcn_exp2f(s_m[s][tid] - mt);
+      s_w[s][tid] = w;
+      lt += w * s_l[s][tid];
+    }
+    ml[tid * 2 + 0] = mt;
+    ml[tid * 2 + 1] = lt;
+  }
+  __syncthreads();
+  float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {
+    const int h = i / D, dd = i % D;
+    float acc = 0.f;
+    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][h][dd], acc);
+    po[i] = acc;
+  }
+}
+
+// Final log-sum-exp merge of the splits and the 1/l normalisation; one workgroup
+// per (problem, head), one lane per output element.
+template <typename E>
+__global__ void attn_combine_kernel(const float* __restrict__ part_ml,
+                                    const float* __restrict__ part_o,
+                                    typename E::storage* __restrict__ out, int q_per_kv, int D,
+                                    int n_splits) {
+  const int ph = blockIdx.x;  // p * q_per_kv + h  == b * H_q + (k * q_per_kv + h)
+  const int p = ph / q_per_kv, h = ph % q_per_kv;
+  const int dd = threadIdx.x;
+  const float* ml = part_ml + (size_t)p * n_splits * q_per_kv * 2;
+  float mt = kNegBig;
+  for (int s = 0; s < n_splits; ++s) mt = fmaxf(mt, ml[((size_t)s * q_per_kv + h) * 2]);
+  float lt = 0.f, acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float w = __builtin_amdgcn_exp2f(ml[((size_t)s * q_per_kv + h) * 2] - mt);
+    lt = fmaf(w, ml[((size_t)s * q_per_kv + h) * 2 + 1], lt);
+    acc = fmaf(w, part_o[(((size_t)p * n_splits + s) * q_per_kv + h) * D + dd], acc);
+  }
+  const float r = acc / lt;
+  if constexpr (E::kBytes == 2) out[(size_t)ph * D + dd] = float_to_bf16_bits(r);
+  else out[(size_t)ph * D + dd] = r;
+}
+
+namespace {
+
+template <typename E, int D, int QPK>
+hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, const void* K,
+                          const void* V, const int32_t* idx, float* part_ml, float* part_o,
+                          hipStream_t st) {
+  using S = typename E::storage;
+  int log2G = 0;
+  while ((1 << log2G) < p.group_size) ++log2G;
+  const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
+  dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
+  hipLaunchKernelGGL((attn_partial_kernel<E, D, QPK>), grid, block, 0, st, (const S*)q, (const S*)K,
+                     (const S*)V, idx, part_ml, part_o, p.n_kv_heads, p.ctx_len, p.n_select, log2G,
+                     pl.attn_units, pl.attn_units_per_split, pl.attn_splits, scale * kLog2e);
+  return hipGetLastError();
+}
+
+template <typename E, int D>
+hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const void* K,
+                      const void* V, const int32_t* idx, float* part_ml, float* part_o,
+                      hipStream_t st) {
+  switch (pl.q_per_kv) {
+    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <typename E>
+hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const void* K,
+                    const void* V, const int32_t* idx, float* part_ml, float* part_o,
+                    hipStream_t st) {
+  switch (p.head_dim) {
+    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
+                       const void* V, const int32_t* idx, float* part_ml, float* part_o,
+                       hipStream_t st) {
+  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, st);
+  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, st);
+}
+
+hipError_t launch_combine(const kvs_params& p, const Plan& pl, const float* part_ml,
+                          const float* part_o, void* out, hipStream_t st) {
+  dim3 grid(pl.problems * pl.q_per_kv), block(p.head_dim);
+  if (p.kv_dtype == KVS_BF16)
+    hipLaunchKernelGGL((attn_combine_kernel<BF16Elem>), grid, block, 0, st, part_ml, part_o,
+                       (uint16_t*)out, pl.q_per_kv, p.head_dim, pl.attn_splits);
+  else
+    hipLaunchKernelGGL((attn_combine_kernel<F32Elem>), grid, block, 0, st, part_ml, part_o,
+                       (float*)out, pl.q_per_kv, p.head_dim, pl.attn_splits);
+  return hipGetLastError();
+}
+
+}  // namespace kvs

@@ -1,0 +1,127 @@
+// Device-side helpers shared by the kvswap_hip kernels (gfx950, wave64 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvs {
+
+constexpr int kWave = 64;
+
+// ---- storage element traits ------------------------------------------------
+// A lane always moves 16 bytes per load: 4 fp32 or 8 bf16 values.
+struct F32Elem {
+  using storage = float;
+  static constexpr int kBytes = 4;
+  static constexpr int kPerLane = 4;
+};
+struct BF16Elem {
+  using storage = uint16_t;
+  static constexpr int kBytes = 2;
+  static constexpr int kPerLane = 8;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+
+// fp32 -> bf16 bits, round-to-nearest-even (finite inputs).
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename E>
+__device__ __forceinline__ void unpack16(const uint4& v, float (&f)[E::kPerLane]);
+
+template <>
+__device__ __forceinline__ void unpack16<F32Elem>(const uint4& v, float (&f)[4]) {
+  f[0] = __uint_as_float(v.x);
+  f[1] = __uint_as_float(v.y);
+  f[2] = __uint_as_float(v.z);
+  f[3] = __uint_as_float(v.w);
+}
+
+template <>
+__device__ __forceinline__ void unpack16<BF16Elem>(const uint4& v, float (&f)[8]) {
+  // element 2i is the low half of dword i, element 2i+1 the high half
+  f[0] = __uint_as_float(v.x << 16);
+  f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16);
+  f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16);
+  f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16);
+  f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+// Scalar load of one stored element as fp32 (runtime dtype; cold paths only).
+__device__ __forceinline__ float load_as_float(const void* base, int is_bf16, size_t i) {
+  return is_bf16 ? bf16_bits_to_float(((const uint16_t*)base)[i]) : ((const float*)base)[i];
+}
+
+// ---- cross-lane exchange -----------------------------------------------------
+// xor_lane<M>(x): value of x held by lane (lane ^ M).  DPP where the ISA has a
+// matching pattern (no LDS traffic), the LDS crossbar otherwise.
+template <int MASK>
+__device__ __forceinline__ float xor_lane(float x) {
+  static_assert(MASK == 1 || MASK == 2 || MASK == 4 || MASK == 8 || MASK == 16 || MASK == 32,
+                "power-of-two lane mask below 64");
+  const int xi = __float_as_int(x);
+  int r;
+  if constexpr (MASK == 1) {
+    r = __builtin_amdgcn_update_dpp(xi, xi, 0xB1, 0xF, 0xF, false);  // quad_perm:[1,0,3,2]
+  } else if constexpr (MASK == 2) {
+    r = __builtin_amdgcn_update_dpp(xi, xi, 0x4E, 0xF, 0xF, false);  // quad_perm:[2,3,0,1]
+  } else if constexpr (MASK == 8) {
+    r = __builtin_amdgcn_update_dpp(xi, xi, 0x128, 0xF, 0xF, false); // row_ror:8 == xor 8 in a row of 16
+  } else if constexpr (MASK == 4 || MASK == 16) {
+    r = __builtin_amdgcn_ds_swizzle(xi, (MASK << 10) | 0x1F);        // bit mode: and 0x1f, or 0, xor MASK
+  } else {
+    r = __shfl_xor(xi, 32, kWave);
+  }
+  return __int_as_float(r);
+}
+
+struct OpSum {
+  static __device__ __forceinline__ float apply(float a, float b) { return a + b; }
+};
+struct OpMax {
+  static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); }
+};
+
+// All-reduce over the lanes whose ids differ only in the bits LO <= bit-mask < HI
+// (LO, HI powers of two; LO == HI is a no-op).  Every participating lane ends
+// with the combined value.
+template <typename Op, int LO, int HI>
+__device__ __forceinline__ float allreduce_lanes(float x) {
+  if constexpr (LO < HI) {
+    if constexpr (LO == 4 && HI >= 16) {
+      // strides 4 and 8 inside a row of 16: two rotations cover {l, l+4, l+8, l+12}
+      const int x0 = __float_as_int(x);
+      x = Op::apply(x, __int_as_float(__builtin_amdgcn_update_dpp(x0, x0, 0x124, 0xF, 0xF, false)));  // row_ror:4
+      const int x1 = __float_as_int(x);
+      x = Op::apply(x, __int_as_float(__builtin_amdgcn_update_dpp(x1, x1, 0x128, 0xF, 0xF, false)));  // row_ror:8
+      return allreduce_lanes<Op, 16, HI>(x);
+    } else {
+      x = Op::apply(x, xor_lane<LO>(x));
+      return allreduce_lanes<Op, LO * 2, HI>(x);
+    }
+  }
+  return x;
+}
+
+// Inclusive prefix sum across the wave (lane i receives the sum over lanes 0..i),
+// modulo 2^32.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)v, off, kWave);
+    if (lane >= off) v += up;
+  }
+  return v;
+}
+
+}  // namespace kvs

@@ -1,0 +1,192 @@
+"""Glue for the GPU parity tests: moves seeded inputs to the device, calls the HIP
+path through the C-ABI binding, calls the CPU oracle on the same host arrays, and
+implements the comparison rules (index margin rule, attention error metric)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2511_11907_amd as kv
+from workloads import Config, LayerInputs, make_layer, storage_to_f32
+
+DEV = "cuda:0"
+
+ATTN_TOL = {"f32": 1e-5, "bf16": 2e-2}   # max |o_gpu - o_ref| / max |o_ref| per (b, h) vector
+GS_TOL = 2e-5                            # fp32 accumulation over r <= 128 terms and <= 8 heads
+MARGIN = 1e-4                            # relative margin of the index rule
+
+
+def dt_code(name: str) -> int:
+    return kv.KVS_F32 if name == "f32" else kv.KVS_BF16
+
+
+def to_dev(x: np.ndarray) -> torch.Tensor:
+    """Storage array (float32, uint16 bf16 bits, int32) -> device tensor."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def to_host_storage(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def kv_params(cfg: Config, **over) -> kv.Params:
+    d = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+             head_dim=cfg.head_dim, rank=cfg.rank, ctx_len=cfg.ctx_len,
+             group_size=cfg.group_size, n_select=cfg.n_select,
+             kv_dtype=dt_code(cfg.dtype), meta_dtype=dt_code(cfg.dtype))
+    d.update(over)
+    return kv.Params(**d)
+
+
+def orc_shape(cfg: Config, n_threads: int = 8, **over) -> oracle.Shape:
+    code = oracle.F32 if cfg.dtype == "f32" else oracle.BF16
+    d = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+             head_dim=cfg.head_dim, rank=cfg.rank, ctx_len=cfg.ctx_len,
+             group_size=cfg.group_size, n_select=cfg.n_select, kv_dtype=code, meta_dtype=code,
+             n_threads=n_threads)
+    d.update(over)
+    return oracle.Shape(**d)
+
+
+def workspace(p: kv.Params) -> torch.Tensor:
+    n = kv.kvs_workspace_bytes(p)
+    assert n > 0
+    # poison, so that a kernel relying on zeroed scratch shows up
+    return torch.full((n // 4,), float("nan"), dtype=torch.float32, device=DEV)
+
+
+class DeviceLayer:
+    """Device copies of one layer's inputs."""
+
+    def __init__(self, L: LayerInputs):
+        self.K, self.V, self.q, self.A = to_dev(L.K), to_dev(L.V), to_dev(L.q), to_dev(L.A)
+
+
+# ---- comparison rules ---------------------------------------------------------------
+def check_index_margin(idx_gpu: np.ndarray, gs_ref: np.ndarray, boundary: np.ndarray, what=""):
+    """idx_gpu [M] of one problem against the oracle's scores gs_ref [NG].
+    Every group scoring above (M+1)-th + eps must be selected, every group scoring below
+    M-th - eps must not; inside the band either is accepted.  The set must hold M unique,
+    in-range, ascending indices.  Returns True if the comparison was bit-exact set
+    equality (margin wider than the band)."""
+    M, NG = idx_gpu.shape[0], gs_ref.shape[0]
+    assert idx_gpu.min() >= 0 and idx_gpu.max() < NG, what
+    assert np.all(np.diff(idx_gpu) > 0), f"{what}: idx not strictly ascending"
+    t_hi, t_lo = boundary
+    if not np.isfinite(t_lo):      # M == NG: everything is selected
+        np.testing.assert_array_equal(idx_gpu, np.arange(NG))
+        return True
+    eps = MARGIN * max(abs(t_hi), abs(t_lo), 1e-3 * np.abs(gs_ref).max())
+    sel = np.zeros(NG, bool)
+    sel[idx_gpu] = True
+    must = gs_ref > t_lo + eps
+    must_not = gs_ref < t_hi - eps
+    assert not np.any(must & ~sel), f"{what}: {int((must & ~sel).sum())} clear winners missing"
+    assert not np.any(must_not & sel), f"{what}: {int((must_not & sel).sum())} clear losers selected"
+    return (t_hi - t_lo) > eps
+
+
+def attn_error(out_gpu: np.ndarray, out_ref: np.ndarray) -> float:
+    """max over (b, h) of  max_i |gpu - ref| / max_i |ref|."""
+    g = out_gpu.astype(np.float64).reshape(-1, out_gpu.shape[-1])
+    r = out_ref.reshape(-1, out_ref.shape[-1])
+    return float((np.abs(g - r).max(1) / np.abs(r).max(1)).max())
+
+
+def out_values(t: torch.Tensor) -> np.ndarray:
+    return storage_to_f32(to_host_storage(t)).astype(np.float64)
+
+
+# ---- one full comparison of a small configuration --------------------------------------
+def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bool = True):
+    """Whole path at a size the oracle finishes in seconds: metadata, prediction and
+    selection, attention with the oracle's indices, and the fused decode step."""
+    L = make_layer(cfg, layer)
+    D = DeviceLayer(L)
+    p = kv_params(cfg, reduce=reduce)
+    sh = orc_shape(cfg, reduce=reduce)
+    B, Hk, N, r, M = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.n_select
+    stats = {}
+
+    # metadata: oracle-rounded K_lr is the reference and the input of the next step
+    klr_ref, klr_exact = oracle.build_metadata(sh, L.K, L.A, want_exact=True)
+    if check_meta:
+        klr_gpu = torch.empty((B, Hk, N, r), dtype=D.K.dtype, device=DEV)
+        kv.kvs_build_metadata(p, D.K, D.A, klr_gpu)
+        torch.cuda.synchronize()
+        absdot = np.einsum("bknd,kdr->bknr", np.abs(storage_to_f32(L.K)).astype(np.float64),
+                           np.abs(L.A).astype(np.float64))
+        stats["meta_mismatch"] = compare_metadata(to_host_storage(klr_gpu), klr_ref, klr_exact,
+                                                  absdot, cfg.head_dim, cfg.dtype)
+
+    ws = workspace(p)
+    klr_dev = to_dev(klr_ref)
+    ref = oracle.predict_select(sh, L.q, klr_ref, L.A)
+    idx = torch.full((B, Hk, M), -1, dtype=torch.int32, device=DEV)
+    gs = torch.full((B, Hk, cfg.n_groups), float("nan"), dtype=torch.float32, device=DEV)
+    kv.kvs_predict_select(p, D.q, klr_dev, D.A, idx, gs, ws)
+    torch.cuda.synchronize()
+    gs_h, idx_h = gs.cpu().numpy().astype(np.float64), idx.cpu().numpy()
+    scale = np.abs(ref["gs"]).max()
+    stats["gs_err"] = float(np.abs(gs_h - ref["gs"]).max() / scale)
+    assert stats["gs_err"] <= GS_TOL, stats
+    exact = 0
+    for b in range(B):
+        for k in range(Hk):
+            exact += check_index_margin(idx_h[b, k], ref["gs"][b, k], ref["boundary"][b, k],
+                                        f"{cfg.name} b={b} k={k}")
+            if (ref["boundary"][b, k][0] - ref["boundary"][b, k][1]) > MARGIN * scale:
+                np.testing.assert_array_equal(idx_h[b, k], ref["idx"][b, k])
+    stats["idx_exact_problems"] = int(exact)
+
+    # attention on the oracle's indices
+    out_ref = oracle.sparse_attn(sh, L.q, L.K, L.V, ref["idx"])
+    out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=D.q.dtype, device=DEV)
+    kv.kvs_sparse_decode_attn(p, D.q, D.K, D.V, to_dev(ref["idx"]), out, ws)
+    torch.cuda.synchronize()
+    stats["attn_err"] = attn_error(out_values(out), out_ref)
+    assert stats["attn_err"] <= ATTN_TOL[cfg.dtype], stats
+
+    # whole step in one call; attention is compared on the indices the GPU chose
+    idx2 = torch.full_like(idx, -1)
+    out2 = torch.full_like(out, float("nan"))
+    kv.kvs_decode_step(p, D.q, klr_dev, D.A, D.K, D.V, idx2, None, out2, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx2.cpu().numpy(), idx_h)
+    out_ref2 = out_ref if np.array_equal(idx_h, ref["idx"]) else oracle.sparse_attn(sh, L.q, L.K, L.V, idx_h)
+    stats["step_err"] = attn_error(out_values(out2), out_ref2)
+    assert stats["step_err"] <= ATTN_TOL[cfg.dtype], stats
+    return stats
+
+
+def _ulp(v: np.ndarray, dtype: str) -> np.ndarray:
+    """Spacing of the storage dtype at |v| (normal range)."""
+    if dtype == "f32":
+        return np.spacing(np.abs(v).astype(np.float32)).astype(np.float64)
+    e = np.floor(np.log2(np.maximum(np.abs(v), 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+def compare_metadata(klr_gpu: np.ndarray, klr_ref: np.ndarray, klr_exact: np.ndarray,
+                     absdot: np.ndarray, d: int, dtype: str) -> float:
+    """GPU K_lr (fp32 accumulation over d terms, one rounding) against the oracle's exact
+    fp64 products: every element must lie within half a unit in the last place of the
+    storage dtype plus the fp32 accumulation bound d * 2^-24 * sum_i |K_i A_ij|.  For bf16
+    storage the result must also be bit-identical to the oracle's rounding except where the
+    exact value sits that close to a rounding boundary (a fraction of a per cent).
+    Returns the fraction of elements that differ from the oracle's rounded array."""
+    g = storage_to_f32(klr_gpu).astype(np.float64)
+    r = storage_to_f32(klr_ref).astype(np.float64)
+    acc = d * 2.0 ** -24 * absdot
+    ulp = np.maximum(_ulp(g, dtype), _ulp(klr_exact, dtype))
+    assert np.all(np.abs(g - klr_exact) <= 0.5 * ulp + acc + 1e-300), \
+        "GPU metadata is further from the exact product than rounding + fp32 accumulation allow"
+    frac = float((g != r).mean())
+    if dtype == "bf16":
+        assert frac <= 2e-3, f"too many metadata elements differ from the oracle: {frac}"
+    return frac

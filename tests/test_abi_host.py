@@ -1,0 +1,126 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol include/kvswap_hip.h declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_11907_amd as kv
+from paper_2511_11907_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvswap_hip.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_UNSUP, E_WS, E_DEV, E_ALIGN = range(8)
+
+
+def _declared():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = kv.load_library()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS), names
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert "gfx950" in kv.kvs_version()
+
+
+def test_python_binding_has_the_same_names_as_the_header():
+    for n in _declared():
+        assert callable(getattr(kv, n)), n
+
+
+def test_status_strings():
+    seen = {kv.kvs_status_str(i) for i in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert kv.kvs_status_str(99) == "unknown status"
+
+
+def _p(**kw):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, rank=32, ctx_len=32768,
+                group_size=4, n_select=820)
+    base.update(kw)
+    return kv.Params(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(), OK),
+    (dict(batch=0), E_SHAPE),
+    (dict(n_q_heads=30), E_SHAPE),            # H_q % H_kv
+    (dict(ctx_len=32770), E_SHAPE),           # N % G
+    (dict(n_select=0), E_SHAPE),
+    (dict(n_select=8193), E_SHAPE),           # M > NG
+    (dict(rank=128, head_dim=64), E_SHAPE),   # r > d
+    (dict(softmax_scale=-1.0), E_SHAPE),
+    (dict(kv_dtype=5), E_DTYPE),
+    (dict(meta_dtype=-1), E_DTYPE),
+    (dict(reduce=2), E_DTYPE),
+    (dict(head_dim=96, rank=32), E_UNSUP),
+    (dict(rank=48), E_UNSUP),
+    (dict(group_size=3, ctx_len=32769), E_UNSUP),
+    (dict(group_size=32), E_UNSUP),
+    (dict(n_q_heads=24), E_UNSUP),            # 3 heads per kv head
+    (dict(n_q_heads=128), E_UNSUP),           # 16 heads per kv head
+    (dict(group_size=1, ctx_len=65536, n_select=10), E_UNSUP),  # NG > 32768
+    (dict(group_size=1, ctx_len=32768, n_select=10), OK),
+])
+def test_check_params(kw, code):
+    assert kv.kvs_check_params(_p(**kw)) == code
+    if code != OK:
+        assert kv.kvs_workspace_bytes(_p(**kw)) == 0
+    else:
+        assert kv.kvs_workspace_bytes(_p(**kw)) > 0
+
+
+def test_workspace_covers_scores_and_partials():
+    p = _p()
+    ws = kv.kvs_workspace_bytes(p)
+    assert ws >= 8 * 8192 * 4 + 8 * 4 * 130 * 4      # group scores + at least one split
+    assert ws % 256 == 0
+    assert kv.kvs_workspace_bytes(_p(batch=8)) > ws
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    """Raw calls with fake (never dereferenced) device addresses: every error below is
+    detected on the host, so this is safe without a GPU."""
+    lib = kv.load_library()
+    c = _p()._c()
+    fake = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10004)
+    null = ctypes.c_void_p(0)
+    big = 1 << 30
+    f = lib.kvs_predict_select
+    assert f(None, fake, fake, fake, fake, null, fake, big, null) == E_NULL
+    assert f(ctypes.byref(c), null, fake, fake, fake, null, fake, big, null) == E_NULL
+    assert f(ctypes.byref(c), fake, fake, fake, null, null, fake, big, null) == E_NULL
+    assert f(ctypes.byref(c), fake, odd, fake, fake, null, fake, big, null) == E_ALIGN
+    assert f(ctypes.byref(c), fake, fake, fake, fake, null, null, big, null) == E_WS
+    assert f(ctypes.byref(c), fake, fake, fake, fake, null, fake, 1024, null) == E_WS
+    assert f(ctypes.byref(c), fake, fake, fake, fake, null, odd, big, null) == E_WS
+    g = lib.kvs_sparse_decode_attn
+    assert g(ctypes.byref(c), fake, fake, null, fake, fake, fake, big, null) == E_NULL
+    assert g(ctypes.byref(c), fake, fake, fake, fake, odd, fake, big, null) == E_ALIGN
+    assert g(ctypes.byref(c), fake, fake, fake, fake, fake, fake, 16, null) == E_WS
+    bad = _p(n_select=9000)._c()
+    assert g(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, big, null) == E_SHAPE
+    assert f(ctypes.byref(bad), fake, fake, fake, fake, null, fake, big, null) == E_SHAPE
+    h = lib.kvs_build_metadata
+    assert h(ctypes.byref(c), null, fake, fake, null) == E_NULL
+    assert h(ctypes.byref(c), fake, odd, fake, null) == E_ALIGN
+    unsup = _p(rank=48)._c()
+    assert h(ctypes.byref(unsup), fake, fake, fake, null) == E_UNSUP
+    s = lib.kvs_decode_step
+    assert s(ctypes.byref(c), fake, fake, fake, fake, null, fake, null, fake, fake, big, null) == E_NULL
+    assert s(ctypes.byref(c), fake, fake, fake, fake, fake, fake, null, fake, fake, 64, null) == E_WS
+
+
+def test_binding_refuses_host_tensors():
+    torch = pytest.importorskip("torch")
+    p = _p(ctx_len=64, n_select=2)
+    q = torch.zeros(1, 32, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        kv.kvs_predict_select(p, q, q, q, q, None, None)

@@ -1,0 +1,281 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element
+on the same seeded inputs.  Needs an MI355X: run with  -m gpu."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+import paper_2511_11907_amd as kv  # noqa: E402
+from workloads import PRESETS, Config, budget_to_groups, make_layer, storage_to_f32  # noqa: E402
+
+import gpu_harness as H  # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    # the HIP library must be the thing that runs
+    assert "gfx950" in kv.kvs_version()
+    print("device:", torch.cuda.get_device_name(0), flush=True)
+
+
+def _say(name, stats):
+    print(f"[parity] {name}: " + ", ".join(f"{k}={v:.3g}" if isinstance(v, float) else f"{k}={v}"
+                                           for k, v in stats.items()), flush=True)
+
+
+# ---- the small reference configuration, at its full size --------------------------------
+def test_c1_full_size_fp32():
+    stats = H.run_and_compare(PRESETS["c1"])
+    _say("c1", stats)
+    assert stats["idx_exact_problems"] == 2
+
+
+# ---- scaled versions of the large configurations (several tiles, ragged tails) -----------
+SCALED = {
+    # 10 % of 1024 groups = 102.4 -> 103: the attention unit list is ragged (103 = 6*16 + 7)
+    "c2_small": PRESETS["c2"].replace(name="c2s", batch=2, ctx_len=4096, n_select=103),
+    # a context that is not a multiple of any tile: 1001 groups of 4
+    "c2_ragged": PRESETS["c2"].replace(name="c2r", batch=1, ctx_len=4004, n_select=77),
+    # long-context layout: r=64, G=8 (a group is two K loads and one K_lr load)
+    "c4_small": PRESETS["c4"].replace(name="c4s", batch=1, ctx_len=16384, n_select=256),
+    "c5_small": PRESETS["c5"].replace(name="c5s", layers=1, batch=3, ctx_len=2048, n_select=26),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SCALED))
+def test_scaled_configs(name):
+    stats = H.run_and_compare(SCALED[name])
+    _say(name, stats)
+
+
+# ---- every supported layout of the kernels ------------------------------------------------
+def _variant(name, dtype, Hq, Hk, d, r, G, N, M, B=2):
+    return Config(name, 1, B, Hq, Hk, d, N, r, G, M, dtype, r, 0.1, 8)
+
+
+VARIANTS = [
+    _variant("bf16_d64_r16_g2_qpk2", "bf16", 4, 2, 64, 16, 2, 1536, 50),
+    _variant("bf16_d64_r64_g16_qpk1", "bf16", 2, 2, 64, 64, 16, 2048, 9),
+    _variant("bf16_d128_r128_g1_qpk8", "bf16", 8, 1, 128, 128, 1, 1024, 100),
+    _variant("bf16_d128_r16_g8_qpk4", "bf16", 8, 2, 128, 16, 8, 2048, 31),
+    _variant("f32_d128_r64_g8_qpk1", "f32", 2, 2, 128, 64, 8, 2048, 17),
+    _variant("f32_d128_r128_g4_qpk2", "f32", 4, 2, 128, 128, 4, 1024, 33),
+    _variant("f32_d64_r32_g16_qpk8", "f32", 8, 1, 64, 32, 16, 4096, 5),
+    _variant("f32_d64_r16_g1_qpk4", "f32", 8, 2, 64, 16, 1, 1024, 64),
+    _variant("f32_d64_r64_g2_qpk2", "f32", 4, 2, 64, 64, 2, 520, 7),
+]
+
+
+@pytest.mark.parametrize("cfg", VARIANTS, ids=[c.name for c in VARIANTS])
+def test_layout_variants(cfg):
+    stats = H.run_and_compare(cfg)
+    _say(cfg.name, stats)
+
+
+@pytest.mark.parametrize("cfg", [SCALED["c2_small"], VARIANTS[4], VARIANTS[0]],
+                         ids=["c2s", "f32_g8", "bf16_g2"])
+def test_mean_reduce(cfg):
+    stats = H.run_and_compare(cfg, reduce=kv.KVS_REDUCE_MEAN, check_meta=False)
+    _say(cfg.name + "_mean", stats)
+
+
+# ---- degenerate and edge cases ----------------------------------------------------------------
+def _predict_only(cfg, klr_storage, L, M):
+    p = H.kv_params(cfg, n_select=M)
+    ws = H.workspace(p)
+    idx = torch.full((cfg.batch, cfg.n_kv_heads, M), -1, dtype=torch.int32, device=H.DEV)
+    kv.kvs_predict_select(p, H.to_dev(L.q), H.to_dev(klr_storage), H.to_dev(L.A), idx, None, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_select_everything_equals_dense_attention(dtype):
+    cfg = SCALED["c2_small"].replace(dtype=dtype, ctx_len=2048, n_select=512, batch=1)
+    L = make_layer(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    idx = _predict_only(cfg, klr, L, 512)
+    np.testing.assert_array_equal(idx, np.tile(np.arange(512, dtype=np.int32), (1, cfg.n_kv_heads, 1)))
+    p = H.kv_params(cfg)
+    D = H.DeviceLayer(L)
+    out = torch.empty((1, cfg.n_q_heads, cfg.head_dim), dtype=D.q.dtype, device=H.DEV)
+    kv.kvs_sparse_decode_attn(p, D.q, D.K, D.V, H.to_dev(idx), out, H.workspace(p))
+    torch.cuda.synchronize()
+    dense = oracle.dense_attn(sh, L.q, L.K, L.V)
+    err = H.attn_error(H.out_values(out), dense)
+    _say(f"dense_equiv_{dtype}", {"err": err})
+    assert err <= H.ATTN_TOL[dtype]
+
+
+def test_single_group_selection():
+    cfg = SCALED["c2_small"].replace(n_select=1)
+    stats = H.run_and_compare(cfg, check_meta=False)
+    _say("M=1", stats)
+
+
+def test_ties_go_to_the_lower_index_and_all_equal_scores():
+    cfg = SCALED["c2_small"].replace(batch=1, ctx_len=4096)
+    L = make_layer(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    # (a) every metadata row identical -> every group score equal -> first M groups
+    flat = np.broadcast_to(klr[:, :, :1, :], klr.shape).copy()
+    for M in (1, 37, 1023, 1024):
+        idx = _predict_only(cfg, flat, L, M)
+        np.testing.assert_array_equal(idx, np.tile(np.arange(M, dtype=np.int32), (1, cfg.n_kv_heads, 1)))
+    # (b) duplicated groups straddling the selection boundary: oracle and GPU agree exactly
+    dup = klr.copy()
+    G = cfg.group_size
+    ref0 = oracle.predict_select(sh, L.q, klr, L.A)
+    for k in range(cfg.n_kv_heads):
+        order = np.argsort(-ref0["gs"][0, k], kind="stable")
+        src = order[cfg.n_select - 1]            # the group sitting exactly at rank M
+        for tgt in (5, 700, 1001):
+            if tgt != src:
+                dup[0, k, tgt * G:(tgt + 1) * G] = dup[0, k, src * G:(src + 1) * G]
+    ref = oracle.predict_select(sh, L.q, dup, L.A)
+    idx = _predict_only(cfg, dup, L, cfg.n_select)
+    np.testing.assert_array_equal(idx, ref["idx"])
+
+
+def test_negative_zero_and_mixed_sign_scores_order_correctly():
+    """Scores straddle zero (mean query is zero-centred), so the order-preserving key map is
+    exercised on both signs; a query of all zeros makes every score (+/-)0 -> first M groups."""
+    cfg = SCALED["c2_small"].replace(batch=1)
+    L = make_layer(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    ref = oracle.predict_select(sh, L.q, klr, L.A)
+    assert (ref["gs"] < 0).any() and (ref["gs"] > 0).any()
+    zero_q = np.zeros_like(L.q)
+    Lz = type(L)(L.cfg, L.layer, L.K, L.V, zero_q, L.A)
+    idx = _predict_only(cfg, klr, Lz, 40)
+    np.testing.assert_array_equal(idx, np.tile(np.arange(40, dtype=np.int32), (1, cfg.n_kv_heads, 1)))
+
+
+def test_attention_accepts_shuffled_indices_and_is_deterministic():
+    cfg = SCALED["c2_small"]
+    L = make_layer(cfg)
+    D = H.DeviceLayer(L)
+    p = H.kv_params(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    ref = oracle.predict_select(sh, L.q, klr, L.A)
+    out_ref = oracle.sparse_attn(sh, L.q, L.K, L.V, ref["idx"])
+    rng = np.random.default_rng(0)
+    shuf = ref["idx"].copy()
+    for b in range(cfg.batch):
+        for k in range(cfg.n_kv_heads):
+            rng.shuffle(shuf[b, k])
+    outs = []
+    for idx in (ref["idx"], ref["idx"], shuf):
+        out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=D.q.dtype, device=H.DEV)
+        kv.kvs_sparse_decode_attn(p, D.q, D.K, D.V, H.to_dev(idx), out, H.workspace(p))
+        torch.cuda.synchronize()
+        outs.append(H.to_host_storage(out))
+    np.testing.assert_array_equal(outs[0], outs[1])               # bit-identical reruns
+    assert H.attn_error(storage_to_f32(outs[2]).astype(np.float64), out_ref) <= H.ATTN_TOL["bf16"]
+    # predict/select is deterministic as well
+    a = _predict_only(cfg, klr, L, cfg.n_select)
+    b = _predict_only(cfg, klr, L, cfg.n_select)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_runs_on_a_side_stream():
+    cfg = SCALED["c5_small"]
+    L = make_layer(cfg)
+    D = H.DeviceLayer(L)
+    p = H.kv_params(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    klr_d = H.to_dev(klr)
+    ws = H.workspace(p)
+    idx = torch.empty((cfg.batch, cfg.n_kv_heads, cfg.n_select), dtype=torch.int32, device=H.DEV)
+    out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=D.q.dtype, device=H.DEV)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        kv.kvs_decode_step(p, D.q, klr_d, D.A, D.K, D.V, idx, None, out, ws)
+    s.synchronize()
+    ref = oracle.predict_select(sh, L.q, klr, L.A)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+    out_ref = oracle.sparse_attn(sh, L.q, L.K, L.V, ref["idx"])
+    assert H.attn_error(H.out_values(out), out_ref) <= H.ATTN_TOL["bf16"]
+
+
+# ---- full-size configurations, oracle on sampled problems ------------------------------------------
+def _full_size_sampled(cfg: Config, samples, budgets=None, layer=0):
+    """GPU on the whole batch at the real size; oracle on the sampled (b, k) problems.
+    The metadata of the sampled problems is built by the oracle and written over the
+    GPU-built rows, so both sides score exactly the same K_lr."""
+    L = make_layer(cfg, layer, workers=16)
+    D = H.DeviceLayer(L)
+    p = H.kv_params(cfg)
+    B, Hk, N, r, qpk = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.q_per_kv
+    klr = torch.empty((B, Hk, N, r), dtype=D.K.dtype, device=H.DEV)
+    kv.kvs_build_metadata(p, D.K, D.A, klr)
+    torch.cuda.synchronize()
+    sub = {}
+    for (b, k) in samples:
+        sh1 = H.orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk)
+        K1, V1 = L.K[b:b + 1, k:k + 1], L.V[b:b + 1, k:k + 1]
+        q1, A1 = L.q[b:b + 1, k * qpk:(k + 1) * qpk], L.A[k:k + 1]
+        klr1, exact1 = oracle.build_metadata(sh1, K1, A1, want_exact=True)
+        absdot = np.abs(storage_to_f32(K1)).astype(np.float64)[0, 0] @ np.abs(A1[0]).astype(np.float64)
+        frac = H.compare_metadata(H.to_host_storage(klr[b, k]), klr1[0, 0], exact1[0, 0], absdot,
+                                  cfg.head_dim, cfg.dtype)
+        klr[b, k].copy_(H.to_dev(klr1[0, 0]))
+        sub[(b, k)] = (sh1, K1, V1, q1, A1, klr1, frac)
+    results = {}
+    for M in (budgets or [cfg.n_select]):
+        pM = H.kv_params(cfg, n_select=M)
+        ws = H.workspace(pM)
+        idx = torch.full((B, Hk, M), -1, dtype=torch.int32, device=H.DEV)
+        out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=D.q.dtype, device=H.DEV)
+        kv.kvs_decode_step(pM, D.q, klr, D.A, D.K, D.V, idx, None, out, ws)
+        torch.cuda.synchronize()
+        idx_h, out_h = idx.cpu().numpy(), H.out_values(out)
+        # properties that hold for every problem at any size
+        assert np.all(np.diff(idx_h, axis=-1) > 0) and idx_h.min() >= 0 and idx_h.max() < cfg.n_groups
+        assert np.isfinite(out_h).all()
+        worst = 0.0
+        for (b, k), (sh1, K1, V1, q1, A1, klr1, frac) in sub.items():
+            shM = H.orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk, n_select=M)
+            ref = oracle.predict_select(shM, q1, klr1, A1)
+            H.check_index_margin(idx_h[b, k], ref["gs"][0, 0], ref["boundary"][0, 0], f"{cfg.name} M={M} b={b} k={k}")
+            out_ref = oracle.sparse_attn(shM, q1, K1, V1, idx_h[b:b + 1, k:k + 1])
+            err = H.attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], out_ref)
+            assert err <= H.ATTN_TOL[cfg.dtype], (cfg.name, M, b, k, err)
+            if M == cfg.n_groups:   # 100 % budget: the step is dense attention
+                dense = oracle.dense_attn(shM, q1, K1, V1)
+                assert H.attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], dense) <= H.ATTN_TOL[cfg.dtype]
+            worst = max(worst, err)
+        results[M] = worst
+    _say(cfg.name + "_full", {f"M={m}": e for m, e in results.items()})
+
+
+def test_c2_full_size_sampled():
+    _full_size_sampled(PRESETS["c2"], [(0, 0), (0, 5), (0, 7)])
+
+
+def test_c3_full_size_sampled():
+    _full_size_sampled(PRESETS["c3"], [(0, 1), (3, 4), (7, 7)])
+
+
+def test_c4_full_size_sampled():
+    _full_size_sampled(PRESETS["c4"], [(0, 0), (3, 6)])
+
+
+def test_c5_layer_full_batch_budget_sweep():
+    """One layer of the 36-layer stack at its real batch and context, over the budget sweep
+    2 / 5 / 10 / 25 / 100 % (82 / 205 / 410 / 1024 / 4096 groups); 100 % must be dense."""
+    cfg = PRESETS["c5"]
+    budgets = [budget_to_groups(x, cfg.n_groups) for x in (0.02, 0.05, 0.10, 0.25, 1.0)]
+    assert budgets == [82, 205, 410, 1024, 4096]
+    _full_size_sampled(cfg, [(0, 0), (9, 3), (15, 7)], budgets=budgets, layer=17)
