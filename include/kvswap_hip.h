@@ -123,6 +123,10 @@ kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
 /* Static, NUL-terminated description of a status code (host pointer). */
 const char* kvs_status_str(kvs_status s);
 
+/* Text of the HIP error behind the calling thread's most recent KVS_ERR_DEVICE
+ * ("" if none yet); diagnostics only (host pointer, static storage). */
+const char* kvs_last_device_error(void);
+
 /* Library version string, e.g. "kvswap_hip 0.1 gfx950" (host pointer). */
 const char* kvs_version(void);
 

@@ -19,14 +19,15 @@ KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
 EXPORTS = (
     "kvs_workspace_bytes", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
-    "kvs_sparse_decode_attn", "kvs_decode_step", "kvs_status_str", "kvs_version",
+    "kvs_sparse_decode_attn", "kvs_decode_step", "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
 
 class KvsError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
-        super().__init__(f"{what}: status {status} ({kvs_status_str(status)})")
+        detail = f": {kvs_last_device_error()}" if status == 6 else ""
+        super().__init__(f"{what}: status {status} ({kvs_status_str(status)}){detail}")
 
 
 class _CParams(ctypes.Structure):
@@ -80,6 +81,10 @@ def load_library() -> ctypes.CDLL:
     path = library_path()
     if not os.path.exists(path):
         _build.build()
+    # torch ships its own HIP runtime (same soname as the system one).  Importing torch
+    # first makes the loader resolve this library against that already-loaded runtime,
+    # so the process has one runtime and device pointers mean the same thing to both.
+    _torch()
     lib = ctypes.CDLL(path)
     vp, pp, sz = ctypes.c_void_p, ctypes.POINTER(_CParams), ctypes.c_size_t
     lib.kvs_workspace_bytes.argtypes = [pp]
@@ -100,6 +105,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_decode_step.restype = ctypes.c_int
     lib.kvs_status_str.argtypes = [ctypes.c_int]
     lib.kvs_status_str.restype = ctypes.c_char_p
+    lib.kvs_last_device_error.argtypes = []
+    lib.kvs_last_device_error.restype = ctypes.c_char_p
     lib.kvs_version.argtypes = []
     lib.kvs_version.restype = ctypes.c_char_p
     _lib = lib
@@ -153,6 +160,10 @@ def _check(status: int, what: str):
 # ---- entry points ---------------------------------------------------------------
 def kvs_status_str(status: int) -> str:
     return load_library().kvs_status_str(int(status)).decode()
+
+
+def kvs_last_device_error() -> str:
+    return load_library().kvs_last_device_error().decode()
 
 
 def kvs_version() -> str:

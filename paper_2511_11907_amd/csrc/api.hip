@@ -97,7 +97,14 @@ kvs_status check_workspace(const Plan& pl, const void* ws, size_t bytes) {
   return KVS_OK;
 }
 
-inline kvs_status dev(hipError_t e) { return e == hipSuccess ? KVS_OK : KVS_ERR_DEVICE; }
+// Text of the most recent HIP error seen by this thread (diagnostics only).
+thread_local const char* g_last_device_error = "";
+
+inline kvs_status dev(hipError_t e) {
+  if (e == hipSuccess) return KVS_OK;
+  g_last_device_error = hipGetErrorString(e);
+  return KVS_ERR_DEVICE;
+}
 
 }  // namespace
 }  // namespace kvs
@@ -203,6 +210,8 @@ const char* kvs_status_str(kvs_status s) {
   }
   return "unknown status";
 }
+
+const char* kvs_last_device_error(void) { return g_last_device_error; }
 
 const char* kvs_version(void) { return "kvswap_hip 0.1 gfx950"; }
 
