@@ -1,0 +1,333 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the KVSwap hot path on one MI355X.
+
+A "step" is one pass of the whole path (low-rank prediction over K_lr, group max,
+top-M groups, attention over the gathered groups) for one batch of one layer
+(all 36 layers for the c5 workload), on seeded synthetic tensors that are already
+resident in HBM.  Steps rotate over several independent copies of the inputs so
+that the working set of consecutive steps exceeds the on-chip caches (the 32K,
+batch-1 working set alone would fit the 256 MB last-level cache).
+
+    python bench.py --gpus 1 --steps K --warmup W [--config c2] [--mode graph|eager]
+
+prints ONE JSON line: tokens/s (= batch / step latency) as `value`, the latency
+itself in `ms_per_step` / `us_per_layer`, a `roofline` object for the dominant
+kernel (algorithmic bytes / measured kernel time against 8 TB/s) and a
+`cpu_baseline` object (the fp64 CPU oracle timed on this machine's host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "decode step latency (µs/layer) + tokens/s; achieved HBM GB/s vs 8 TB/s peak"
+CACHE_BYTES = 256e6 + 32e6     # last-level cache + the eight L2s
+
+
+# --------------------------------------------------------------------------------------
+# algorithmic bytes: what the method itself has to move per layer-step
+# --------------------------------------------------------------------------------------
+def algorithmic_bytes(cfg) -> dict:
+    P = cfg.batch * cfg.n_kv_heads
+    eb = cfg.elem_bytes
+    NG, M = cfg.n_groups, cfg.n_select
+    q_bytes = cfg.batch * cfg.n_q_heads * cfg.head_dim * eb
+    a_bytes = cfg.n_kv_heads * cfg.head_dim * cfg.rank * 4
+    predict = P * cfg.ctx_len * cfg.rank * eb + q_bytes + a_bytes + P * NG * 4
+    topk = P * NG * 4 + P * M * 4
+    attn = P * M * 4 + 2 * P * M * cfg.group_size * cfg.head_dim * eb + q_bytes + q_bytes
+    return {"predict": predict, "topk": topk, "predict_select": predict + topk, "attn": attn,
+            "step": predict + topk + attn}
+
+
+# --------------------------------------------------------------------------------------
+# workload: device-resident rotating copies
+# --------------------------------------------------------------------------------------
+class Workload:
+    def __init__(self, cfg, copies: int, log=print):
+        import torch
+        import paper_2511_11907_amd as kv
+        from workloads import make_layer
+
+        self.cfg, self.kv, self.torch = cfg, kv, torch
+        dev = "cuda:0"
+        code = kv.KVS_F32 if cfg.dtype == "f32" else kv.KVS_BF16
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        self.p = kv.Params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank,
+                           cfg.ctx_len, cfg.group_size, cfg.n_select, code, code)
+        self.ws = torch.empty(kv.kvs_workspace_bytes(self.p) // 4, dtype=torch.float32, device=dev)
+        kv.kvs_workspace_init(self.p, self.ws)
+        self.slots = []
+        self.host0 = None
+        B, Hk, N = cfg.batch, cfg.n_kv_heads, cfg.ctx_len
+
+        def up(x):
+            import numpy as np
+            if x.dtype == np.uint16:
+                return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+            return torch.from_numpy(x).to(dev)
+
+        # c5: the copies ARE the 36 layers (distinct adapters); otherwise independent
+        # sequences of layer 0 that share layer 0's adapter
+        per_layer = cfg.layers > 1
+        n = cfg.layers if per_layer else copies
+        A0 = None
+        t0 = time.time()
+        for c in range(n):
+            if per_layer:
+                L = make_layer(cfg, layer=c, workers=16)
+            else:
+                L = make_layer(cfg, layer=0, workers=16, seq_offset=c * B, adapter_from=A0)
+                A0 = L.A
+            s = {"K": up(L.K), "V": up(L.V), "q": up(L.q), "A": up(L.A)}
+            s["K_lr"] = torch.empty((B, Hk, N, cfg.rank), dtype=tdt, device=dev)
+            kv.kvs_build_metadata(self.p, s["K"], s["A"], s["K_lr"])
+            s["idx"] = torch.empty((B, Hk, cfg.n_select), dtype=torch.int32, device=dev)
+            s["gs"] = torch.empty((B, Hk, cfg.n_groups), dtype=torch.float32, device=dev)
+            s["out"] = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=tdt, device=dev)
+            self.slots.append(s)
+            if c == 0:
+                self.host0 = L
+            del L
+        torch.cuda.synchronize()
+        log(f"[bench] {cfg.name}: {n} input copies resident ({time.time() - t0:.1f}s to generate)")
+        self.layers_per_step = cfg.layers if per_layer else 1
+
+    # one layer-step on slot i through the single fused entry point
+    def layer_step(self, i: int):
+        s = self.slots[i % len(self.slots)]
+        self.kv.kvs_decode_step(self.p, s["q"], s["K_lr"], s["A"], s["K"], s["V"], s["idx"], None,
+                                s["out"], self.ws)
+
+    def step(self, i: int):
+        if self.layers_per_step == 1:
+            self.layer_step(i)
+        else:
+            for l in range(self.layers_per_step):
+                self.layer_step(l)
+
+
+def time_steps(wl: Workload, steps: int, warmup: int, mode: str) -> float:
+    """Seconds for exactly `steps` steps (after `warmup` untimed ones)."""
+    torch = wl.torch
+    n = len(wl.slots) if wl.layers_per_step == 1 else 1   # steps per rotation
+    if mode == "eager":
+        for i in range(warmup):
+            wl.step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            wl.step(i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+    # graph mode: one captured rotation (n steps), plus a tail graph if steps % n != 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for i in range(max(2, min(warmup, n))):
+            wl.step(i)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    def capture(count):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(count):
+                wl.step(i)
+        return g
+
+    full, tail = divmod(steps, n)
+    g_full = capture(n) if full else None
+    g_tail = capture(tail) if tail else None
+    for _ in range(max(1, warmup // n)):
+        (g_full or g_tail).replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(full):
+        g_full.replay()
+    if g_tail is not None:
+        g_tail.replay()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def time_kernels(wl: Workload, reps: int) -> dict:
+    """Average duration of each kernel family, from HIP events on the launch stream:
+    `reps` back-to-back launches over the rotating copies between two events (so the
+    figure includes the gap between consecutive launches and is an upper bound on the
+    kernel's own duration)."""
+    torch, kv, p = wl.torch, wl.kv, wl.p
+
+    def timed(fn):
+        for i in range(min(reps, 2 * len(wl.slots))):
+            fn(wl.slots[i % len(wl.slots)])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(wl.slots[i % len(wl.slots)])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps   # us
+
+    out = {}
+    # the two launches of a step ...
+    out["predict_select"] = timed(lambda s: kv.kvs_predict_select(p, s["q"], s["K_lr"], s["A"], s["idx"], None, wl.ws))
+    out["attn"] = timed(lambda s: kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], wl.ws))
+    # ... and, for reference, the streaming part of the first one without the selection tail
+    out["predict_scores_only"] = timed(lambda s: kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"]))
+    out["topk_only"] = timed(lambda s: kv.kvs_select_topk(p, s["gs"], s["idx"]))
+    return out
+
+
+def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
+    """The fp64 oracle as it stands, single-threaded, on the same inputs: whole steps
+    (prediction + selection + sparse attention) of copy 0 until ~budget_s seconds."""
+    import numpy as np
+    import oracle
+
+    code = oracle.F32 if cfg.dtype == "f32" else oracle.BF16
+    # bound the sample: at most 8 (sequence, kv head) problems of the batch
+    P = cfg.batch * cfg.n_kv_heads
+    nb = max(1, min(cfg.batch, 8 // cfg.n_kv_heads if cfg.n_kv_heads <= 8 else 1))
+    sh = oracle.Shape(nb, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank, cfg.ctx_len,
+                      cfg.group_size, cfg.n_select, code, code, n_threads=1)
+    K, V, q = (np.ascontiguousarray(x[:nb]) for x in (L.K, L.V, L.q))
+    klr = oracle.build_metadata(oracle.Shape(**{**sh.__dict__, "n_threads": 8}), K, L.A)  # untimed set-up
+    reps, spent = 0, 0.0
+    while spent < budget_s and reps < 50:
+        t0 = time.perf_counter()
+        r = oracle.predict_select(sh, q, klr, L.A)
+        oracle.sparse_attn(sh, q, K, V, r["idx"])
+        spent += time.perf_counter() - t0
+        reps += 1
+    tokens = reps * nb                      # sequences advanced by one token
+    frac = nb * cfg.n_kv_heads / P          # share of one layer-step that was timed
+    return {"value": tokens / spent / cfg.layers, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{reps} x (predict_select + sparse_attn) of {nb} of {cfg.batch} sequences, "
+                      f"{cfg.n_kv_heads} kv heads, one layer, fp64 single thread; "
+                      f"{spent / reps * 1e3:.1f} ms per sampled layer-step "
+                      f"({frac:.3g} of a full layer-step); value scaled to all {cfg.layers} layer(s)"}
+
+
+def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> dict:
+    ab = algorithmic_bytes(cfg)
+    if copies is None:
+        copies = max(2, int(-(-3 * CACHE_BYTES // ab["step"])))   # rotation >= 3x the caches
+        copies = min(copies, 32)
+    wl = Workload(cfg, copies, log)
+    sec = time_steps(wl, steps, warmup, mode)
+    ms_step = sec / steps * 1e3
+    layers = wl.layers_per_step
+    us_layer = ms_step * 1e3 / layers
+    kern = time_kernels(wl, max(steps, 50))
+    # warm-cache figure for reference: the same step repeated on one copy
+    one = Workload.__new__(Workload)
+    one.__dict__.update(wl.__dict__)
+    one.slots = wl.slots[:1] if layers == 1 else wl.slots
+    warm_ms = time_steps(one, steps, warmup, mode) / steps * 1e3 if layers == 1 else None
+    dom = max(("predict_select", "attn"), key=lambda k: kern[k])
+    achieved = ab[dom] / (kern[dom] * 1e-6) / 1e9
+    res = {
+        "tokens_per_s": cfg.batch / (ms_step * 1e-3),
+        "ms_per_step": ms_step,
+        "us_per_layer": us_layer,
+        "step_gbps": ab["step"] * layers / (ms_step * 1e-3) / 1e9,
+        "kernel_us": kern,
+        "dominant": dom,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": ab[dom], "kernel_us": kern[dom]},
+        "algorithmic_bytes": ab,
+        "copies": len(wl.slots),
+        "warm_ms_per_step": warm_ms,
+    }
+    if want_cpu:
+        res["cpu_baseline"] = cpu_baseline(cfg, wl.host0)
+    del wl, one
+    import torch
+    torch.cuda.empty_cache()
+    return res
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=24)
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--copies", type=int, default=None, help="rotating input copies (default: 3x the caches)")
+    ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from workloads import PRESETS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    import paper_2511_11907_amd as kv
+    log(f"[bench] {kv.kvs_version()} from {kv.library_path()} on {torch.cuda.get_device_name(0)}")
+
+    cfg = PRESETS[args.config]
+    main_res = measure(cfg, args.steps, args.warmup, args.mode, args.copies, log,
+                       want_cpu=not args.no_cpu_baseline)
+    others = {}
+    for name in [x for x in args.extra.split(",") if x and x != args.config]:
+        c = PRESETS[name]
+        st = max(20, min(args.steps, 60))
+        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False)
+        others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
+                                          "roofline", "copies")}
+        others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
+
+    line = {
+        "metric": METRIC,
+        "value": main_res["tokens_per_s"],
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "us_per_layer": main_res["us_per_layer"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv d={cfg.head_dim} "
+                               f"N={cfg.ctx_len} b={cfg.batch} r={cfg.rank} G={cfg.group_size} "
+                               f"M={cfg.n_select} layers={cfg.layers} {cfg.dtype}",
+                   "mode": args.mode, "input_copies": main_res["copies"]},
+        "step_hbm_gbps": main_res["step_gbps"],
+        "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
+        "warm_ms_per_step": main_res["warm_ms_per_step"],
+        "kernel_us": main_res["kernel_us"],
+        "algorithmic_bytes": main_res["algorithmic_bytes"],
+        "roofline": main_res["roofline"],
+    }
+    if "cpu_baseline" in main_res:
+        line["cpu_baseline"] = main_res["cpu_baseline"]
+    if others:
+        line["other_workloads"] = others
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -30,8 +30,16 @@
  * frees nothing, keeps no state between calls and never synchronises; all work
  * is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  * stream).  Inputs are read-only.  `workspace` is caller-provided scratch of at
- * least kvs_workspace_bytes() bytes; its contents are undefined on entry and on
- * return, and two calls that share a workspace must be ordered on one stream.
+ * least kvs_workspace_bytes() bytes.  It starts with a small area of counters
+ * (per-problem score histograms, and the arrival counters with which the
+ * attention kernel hands the final merge to the workgroup that finishes last)
+ * that must be zero when a call starts: call kvs_workspace_init once after
+ * allocating (or zero-fill the buffer yourself); every call then leaves the
+ * counters zero for the next one.
+ * The rest of the workspace is undefined on entry and on return.  Calls that
+ * share a workspace must be ordered on one stream (they would race otherwise),
+ * and a workspace prepared for one kvs_params serves any params that need no
+ * more bytes.
  *
  * Errors: every function validates its arguments on the host before anything is
  * launched and returns a kvs_status; nothing is thrown or aborted across the
@@ -79,6 +87,11 @@ typedef struct {
  * (0 if the params are invalid). */
 size_t kvs_workspace_bytes(const kvs_params* p);
 
+/* Zero the arrival counters at the start of `workspace` (one small fill kernel
+ * on `stream`).  Needed once per workspace buffer, before its first use. */
+kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
 /* Validate params without touching a device: KVS_OK or the error the other
  * calls would return for them. */
 kvs_status kvs_check_params(const kvs_params* p);
@@ -92,14 +105,16 @@ kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A
 /* Sec. 4.3 (Eq. 1, "Scoring and selection"): low-rank token scores summed over
  * the query heads of each KV head, group representative (max or mean), and the
  * indices of the M best groups per (b, kv head): ties go to the lower index,
- * output ascending.  group_scores may be NULL; if given it receives gs. */
+ * output ascending.  Two launches: the streaming kernel also histograms the
+ * scores, the selection kernel starts from that histogram.  group_scores may be
+ * NULL; if given it receives gs. */
 kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_lr,
                               const float* A, int32_t* idx, float* group_scores,
                               void* workspace, size_t workspace_bytes, void* stream);
 
-/* The two halves of kvs_predict_select as separate calls (same arithmetic, same
- * kernels): kvs_predict_scores writes group_scores [B,H_kv,N/G] (required here),
- * kvs_select_topk reads them and writes idx.  Neither needs a workspace. */
+/* The two halves of kvs_predict_select as separate launches (same arithmetic, same
+ * device routines): kvs_predict_scores writes group_scores [B,H_kv,N/G] (required
+ * here), kvs_select_topk reads them and writes idx.  Neither needs a workspace. */
 kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr,
                               const float* A, float* group_scores, void* stream);
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
@@ -107,13 +122,14 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
 
 /* Sec. 4.4 (attention consumes only the selected KV groups): softmax attention
  * of every query head over the G*M tokens named by idx of its KV head, gathered
- * from the full K/V, fp32 online softmax, result rounded to kv_dtype. */
+ * from the full K/V, fp32 online softmax, result rounded to kv_dtype.  One
+ * launch (split over the selected groups, merged by the last workgroup). */
 kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K,
                                   const void* V, const int32_t* idx, void* out,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* One whole decode step of a layer: kvs_predict_select followed by
- * kvs_sparse_decode_attn on the same stream with the fewest launches.  idx
+ * kvs_sparse_decode_attn on the same stream (three launches in all).  idx
  * receives the selection (it is an output here); group_scores may be NULL. */
 kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
                            const float* A, const void* K, const void* V, int32_t* idx,

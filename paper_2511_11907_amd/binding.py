@@ -17,7 +17,7 @@ KVS_F32, KVS_BF16 = 0, 1
 KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
 
 EXPORTS = (
-    "kvs_workspace_bytes", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
+    "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
     "kvs_sparse_decode_attn", "kvs_decode_step", "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
@@ -69,7 +69,8 @@ _lib = None
 
 
 def library_path() -> str:
-    return _build.LIB
+    """The in-tree library, unless KVSWAP_HIP_LIBRARY names another build of it."""
+    return os.environ.get("KVSWAP_HIP_LIBRARY") or _build.LIB
 
 
 def load_library() -> ctypes.CDLL:
@@ -89,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     vp, pp, sz = ctypes.c_void_p, ctypes.POINTER(_CParams), ctypes.c_size_t
     lib.kvs_workspace_bytes.argtypes = [pp]
     lib.kvs_workspace_bytes.restype = sz
+    lib.kvs_workspace_init.argtypes = [pp, vp, sz, vp]
+    lib.kvs_workspace_init.restype = ctypes.c_int
     lib.kvs_check_params.argtypes = [pp]
     lib.kvs_check_params.restype = ctypes.c_int
     lib.kvs_build_metadata.argtypes = [pp, vp, vp, vp, vp]
@@ -178,6 +181,13 @@ def kvs_check_params(p: Params) -> int:
 def kvs_workspace_bytes(p: Params) -> int:
     c = p._c()
     return int(load_library().kvs_workspace_bytes(ctypes.byref(c)))
+
+
+def kvs_workspace_init(p: Params, workspace, stream=None) -> None:
+    c = p._c()
+    ws, nws = _ws(workspace)
+    _check(load_library().kvs_workspace_init(ctypes.byref(c), ws, nws, _stream(stream)),
+           "kvs_workspace_init")
 
 
 def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:

@@ -2,6 +2,9 @@
 // declared in include/kvswap_hip.h.  Everything here runs on the host; all checks
 // are done before the first launch.
 #include <math.h>
+#ifdef KVS_TUNING
+#include <stdlib.h>
+#endif
 
 #include "kernels.h"
 
@@ -14,6 +17,20 @@ inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
+// Launch-shape targets.  A tuning build (-DKVS_TUNING) lets the environment override
+// them for sweeps; the shipped library uses the constants.
+inline int target(const char* env_name, int dflt) {
+#ifdef KVS_TUNING
+  if (const char* v = getenv(env_name)) {
+    const int x = atoi(v);
+    if (x > 0) return x;
+  }
+#else
+  (void)env_name;
+#endif
+  return dflt;
+}
+
 }  // namespace
 
 Plan make_plan(const kvs_params& p) {
@@ -22,14 +39,14 @@ Plan make_plan(const kvs_params& p) {
   pl.n_groups = p.ctx_len / p.group_size;
   pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
 
-  // predict: enough workgroups to cover the chip several times, each streaming at
-  // least one full step of 4 waves x 8 loads
+  // predict: one resident wave of workgroups over the whole chip, each streaming at
+  // least one full step of its 16 waves
   const int meta_epl = p.meta_dtype == KVS_BF16 ? 8 : 4;
   pl.meta_lanes_per_row = p.rank / meta_epl;
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;
   pl.predict_units = ceil_div(p.ctx_len, pl.meta_rows_per_unit);
   {
-    const int want = ceil_div(2048, pl.problems);
+    const int want = ceil_div(target("KVS_PREDICT_WGS", kPredictTargetWgs), pl.problems);
     const int most = ceil_div(pl.predict_units, kPredictUnitsPerWgStep);
     const int chunks = want < 1 ? 1 : (want > most ? most : want);
     pl.predict_units_per_wg = round_up(ceil_div(pl.predict_units, chunks), kPredictUnitsPerWgStep);
@@ -42,14 +59,21 @@ Plan make_plan(const kvs_params& p) {
   pl.kv_toks_per_unit = 64 / pl.kv_lanes_per_tok;
   pl.attn_units = ceil_div(p.n_select * p.group_size, pl.kv_toks_per_unit);
   {
-    const int want = ceil_div(1024, pl.problems);
+    const int want = ceil_div(target("KVS_ATTN_WGS", kAttnTargetWgs), pl.problems);
     const int most = ceil_div(pl.attn_units, kAttnUnitsPerWgStep);
-    const int splits = want < 1 ? 1 : (want > most ? most : want);
+    int splits = want < 1 ? 1 : (want > most ? most : want);
+    if (splits > kAttnMaxSplitsPerProblem) splits = kAttnMaxSplitsPerProblem;
     pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWgStep);
     pl.attn_splits = ceil_div(pl.attn_units, pl.attn_units_per_split);
   }
 
   size_t off = 0;
+  // zero-on-entry area: [0, P) attention arrival counters, then one histogram of
+  // kSelectHistBins counters per problem
+  pl.off_sync = off;
+  pl.off_hist = align256((size_t)pl.problems * sizeof(int));
+  pl.sync_bytes = pl.off_hist + align256((size_t)pl.problems * kSelectHistBins * sizeof(int));
+  off += pl.sync_bytes;
   pl.off_gs = off;
   off += align256((size_t)pl.problems * pl.n_groups * sizeof(float));
   pl.off_part_ml = off;
@@ -120,6 +144,16 @@ size_t kvs_workspace_bytes(const kvs_params* p) {
   return make_plan(*p).total_bytes;
 }
 
+kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!p) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  const Plan pl = make_plan(*p);
+  if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+  return dev(launch_fill_zero((char*)workspace + pl.off_sync, pl.sync_bytes, (hipStream_t)stream));
+}
+
 kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A, void* K_lr,
                               void* stream) {
   if (!p || !K || !A || !K_lr) return KVS_ERR_NULL;
@@ -145,8 +179,9 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   float* gs = group_scores ? group_scores : (float*)((char*)workspace + pl.off_gs);
   hipStream_t st = (hipStream_t)stream;
-  if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, st))) != KVS_OK) return s;
-  return dev(launch_topk(*p, pl, gs, idx, st));
+  int* hist = (int*)((char*)workspace + pl.off_hist);
+  if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, hist, st))) != KVS_OK) return s;
+  return dev(launch_topk(*p, pl, gs, idx, hist, st));
 }
 
 kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr, const float* A,
@@ -157,7 +192,7 @@ kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_
   if (misaligned(q) || misaligned(K_lr) || misaligned(A) || misaligned(group_scores))
     return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
-  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, (hipStream_t)stream));
+  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, nullptr, (hipStream_t)stream));
 }
 
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
@@ -167,7 +202,7 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
   if (s != KVS_OK) return s;
   if (misaligned(group_scores) || misaligned(idx)) return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
-  return dev(launch_topk(*p, pl, group_scores, idx, (hipStream_t)stream));
+  return dev(launch_topk(*p, pl, group_scores, idx, nullptr, (hipStream_t)stream));
 }
 
 kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,
@@ -182,9 +217,9 @@ kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
   float* part_o = (float*)((char*)workspace + pl.off_part_o);
-  hipStream_t st = (hipStream_t)stream;
-  if ((s = dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, st))) != KVS_OK) return s;
-  return dev(launch_combine(*p, pl, part_ml, part_o, out, st));
+  int* arrivals = (int*)((char*)workspace + pl.off_sync);
+  return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals,
+                         (hipStream_t)stream));
 }
 
 kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr, const float* A,

@@ -13,6 +13,10 @@
 // with the usual log-sum-exp rescaling.  A group is G consecutive rows, i.e. one
 // contiguous run of G*d elements, so with G*LPT = 64 a unit is exactly one group
 // and every wave-wide load is a fully used 1 KiB burst.
+//
+// The final merge over the splits is done by the workgroup of a problem that finishes
+// last (arrival counter in the workspace, no waiting), so the whole attention is one
+// launch.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -21,6 +25,7 @@ namespace kvs {
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kAttnUnroll = 4;       // units (K load + V load each) in flight per wave
+constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -28,8 +33,9 @@ template <typename E, int D, int QPK>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
-    float* __restrict__ part_ml, float* __restrict__ part_o, int n_kv_heads, int N, int M,
-    int log2G, int units, int units_per_split, int n_splits, float scale_log2e) {
+    float* part_ml, float* part_o, typename E::storage* __restrict__ out,
+    int* __restrict__ arrivals, int n_kv_heads, int N, int M, int log2G, int units,
+    int units_per_split, int n_splits, float scale_log2e) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPT = D / EPL;       // lanes per token row
   constexpr int TPU = kWave / LPT;   // tokens per unit
@@ -159,8 +165,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       for (int e = 0; e < EPL; ++e) s_o[wave][h][c * EPL + e] = o[h][e];
     }
   }
-  __syncthreads();
-  // per head: global max, weights, sum of l
+  lds_barrier();
+  // per head: workgroup max, weights, sum of l
   float* ml = part_ml + ((size_t)p * n_splits + split) * QPK * 2;
   if (tid < QPK) {
     float mt = kNegBig;
@@ -171,41 +177,61 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       s_w[s][tid] = w;
       lt += w * s_l[s][tid];
     }
-    ml[tid * 2 + 0] = mt;
-    ml[tid * 2 + 1] = lt;
+    publish_store(&ml[tid * 2 + 0], mt);
+    publish_store(&ml[tid * 2 + 1], lt);
   }
-  __syncthreads();
+  lds_barrier();
   float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
   for (int i = tid; i < QPK * D; i += kAttnThreads) {
     const int h = i / D, dd = i % D;
     float acc = 0.f;
     for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][h][dd], acc);
-    po[i] = acc;
+    publish_store(&po[i], acc);
   }
-}
 
-// Final log-sum-exp merge of the splits and the 1/l normalisation; one workgroup
-// per (problem, head), one lane per output element.
-template <typename E>
-__global__ void attn_combine_kernel(const float* __restrict__ part_ml,
-                                    const float* __restrict__ part_o,
-                                    typename E::storage* __restrict__ out, int q_per_kv, int D,
-                                    int n_splits) {
-  const int ph = blockIdx.x;  // p * q_per_kv + h  == b * H_q + (k * q_per_kv + h)
-  const int p = ph / q_per_kv, h = ph % q_per_kv;
-  const int dd = threadIdx.x;
-  const float* ml = part_ml + (size_t)p * n_splits * q_per_kv * 2;
-  float mt = kNegBig;
-  for (int s = 0; s < n_splits; ++s) mt = fmaxf(mt, ml[((size_t)s * q_per_kv + h) * 2]);
-  float lt = 0.f, acc = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float w = __builtin_amdgcn_exp2f(ml[((size_t)s * q_per_kv + h) * 2] - mt);
-    lt = fmaf(w, ml[((size_t)s * q_per_kv + h) * 2 + 1], lt);
-    acc = fmaf(w, part_o[(((size_t)p * n_splits + s) * q_per_kv + h) * D + dd], acc);
+  // ---- the last workgroup of the problem merges the splits ------------------------
+  __shared__ int s_last;
+  __shared__ float s_cw[QPK][kAttnMaxSplits];  // weight of each split, per head
+  __shared__ float s_cl[QPK];                  // merged softmax denominators
+  publish_complete_and_barrier();  // the partials are out before the arrival is announced
+  if (tid == 0) {
+    const int old = atomicAdd(&arrivals[p], 1);
+    s_last = (old == n_splits - 1);
+    if (s_last) arrivals[p] = 0;  // leave the counter ready for the next call
   }
-  const float r = acc / lt;
-  if constexpr (E::kBytes == 2) out[(size_t)ph * D + dd] = float_to_bf16_bits(r);
-  else out[(size_t)ph * D + dd] = r;
+  lds_barrier();
+  if (!s_last) return;
+  const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
+  for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
+    float mt = kNegBig;
+    for (int s = lane; s < n_splits; s += kWave) mt = fmaxf(mt, load_published(&pml[((size_t)s * QPK + h) * 2]));
+    mt = allreduce_lanes<OpMax, 1, kWave>(mt);
+    float lt = 0.f;
+    for (int s = lane; s < n_splits; s += kWave) {
+      const float w = __builtin_amdgcn_exp2f(load_published(&pml[((size_t)s * QPK + h) * 2]) - mt);
+      s_cw[h][s] = w;
+      lt = fmaf(w, load_published(&pml[((size_t)s * QPK + h) * 2 + 1]), lt);
+    }
+    lt = allreduce_lanes<OpSum, 1, kWave>(lt);
+    if (lane == 0) s_cl[h] = lt;
+  }
+  lds_barrier();
+  const float* ppo = part_o + (size_t)p * n_splits * QPK * D;
+  typename E::storage* op = out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {
+    const int h = i / D;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 4 <= n_splits; s += 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[j] = fmaf(s_cw[h][s + j], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
+    }
+    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[h][s], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
+    const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
+    if constexpr (E::kBytes == 2) op[i] = float_to_bf16_bits(r);
+    else op[i] = r;
+  }
 }
 
 namespace {
@@ -213,14 +239,15 @@ namespace {
 template <typename E, int D, int QPK>
 hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                           const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                          hipStream_t st) {
+                          void* out, int* arrivals, hipStream_t st) {
   using S = typename E::storage;
   int log2G = 0;
   while ((1 << log2G) < p.group_size) ++log2G;
   const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
   hipLaunchKernelGGL((attn_partial_kernel<E, D, QPK>), grid, block, 0, st, (const S*)q, (const S*)K,
-                     (const S*)V, idx, part_ml, part_o, p.n_kv_heads, p.ctx_len, p.n_select, log2G,
+                     (const S*)V, idx, part_ml, part_o, (S*)out, arrivals, p.n_kv_heads, p.ctx_len,
+                     p.n_select, log2G,
                      pl.attn_units, pl.attn_units_per_split, pl.attn_splits, scale * kLog2e);
   return hipGetLastError();
 }
@@ -228,12 +255,12 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
 template <typename E, int D>
 hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                       const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                      hipStream_t st) {
+                      void* out, int* arrivals, hipStream_t st) {
   switch (pl.q_per_kv) {
-    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, st);
-    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, st);
-    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, st);
-    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
   }
   return hipErrorInvalidValue;
 }
@@ -241,10 +268,10 @@ hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const 
 template <typename E>
 hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                     const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                    hipStream_t st) {
+                    void* out, int* arrivals, hipStream_t st) {
   switch (p.head_dim) {
-    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, st);
-    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, st);
+    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
   }
   return hipErrorInvalidValue;
 }
@@ -253,21 +280,9 @@ hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const vo
 
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       hipStream_t st) {
-  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, st);
-  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, st);
-}
-
-hipError_t launch_combine(const kvs_params& p, const Plan& pl, const float* part_ml,
-                          const float* part_o, void* out, hipStream_t st) {
-  dim3 grid(pl.problems * pl.q_per_kv), block(p.head_dim);
-  if (p.kv_dtype == KVS_BF16)
-    hipLaunchKernelGGL((attn_combine_kernel<BF16Elem>), grid, block, 0, st, part_ml, part_o,
-                       (uint16_t*)out, pl.q_per_kv, p.head_dim, pl.attn_splits);
-  else
-    hipLaunchKernelGGL((attn_combine_kernel<F32Elem>), grid, block, 0, st, part_ml, part_o,
-                       (float*)out, pl.q_per_kv, p.head_dim, pl.attn_splits);
-  return hipGetLastError();
+                       void* out, int* arrivals, hipStream_t st) {
+  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
 }
 
 }  // namespace kvs

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) s_k[r_ * ld + cc * EPL + e] = f[e];
   }
-  __syncthreads();
+  lds_barrier();
 
   const int row = tid & (kMetaRows - 1);
   const int jq = __builtin_amdgcn_readfirstlane(tid / kMetaRows);  // wave-uniform column quarter

@@ -61,6 +61,17 @@ __device__ __forceinline__ float load_as_float(const void* base, int is_bf16, si
   return is_bf16 ? bf16_bits_to_float(((const uint16_t*)base)[i]) : ((const float*)base)[i];
 }
 
+// ---- workgroup barrier for LDS traffic only ----------------------------------------------
+// __syncthreads() also waits for every outstanding global load and store of the wave,
+// which serialises the memory latency the kernels work to overlap (prefetched tiles,
+// scattered result stores).  Wherever only LDS contents have to be ordered, this barrier
+// is used instead: it waits for the wave's LDS operations alone.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---- cross-lane exchange -----------------------------------------------------
 // xor_lane<M>(x): value of x held by lane (lane ^ M).  DPP where the ISA has a
 // matching pattern (no LDS traffic), the LDS crossbar otherwise.
@@ -112,16 +123,36 @@ __device__ __forceinline__ float allreduce_lanes(float x) {
   return x;
 }
 
-// Inclusive prefix sum across the wave (lane i receives the sum over lanes 0..i),
-// modulo 2^32.
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t up = (uint32_t)__shfl_up((int)v, off, kWave);
-    if (lane >= off) v += up;
-  }
-  return v;
+// ---- handing results to another workgroup ----------------------------------------------
+// The streaming kernels finish a problem in whichever workgroup arrives last at a
+// per-problem counter.  Workgroups of one problem run on different XCDs, whose L2
+// caches are not coherent with each other, and a device-scope fence costs a sweep of
+// the whole L2 per workgroup (measured: it multiplies the kernel time).  So the few
+// values that cross workgroups are moved with device-scope accesses instead, which go
+// past the non-coherent cache levels: the publisher writes them with device-scope
+// stores (and device-scope atomics), waits until the memory system has acknowledged
+// them, and only then bumps the arrival counter; the last workgroup reads them with
+// device-scope loads.  No cache is flushed or invalidated, and nobody ever waits on
+// another workgroup.
+
+__device__ __forceinline__ void publish_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float load_published(const float* p) {
+  return __hip_atomic_load(const_cast<float*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int load_published(const int* p) {
+  return __hip_atomic_load(const_cast<int*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Every lane calls this after its last publish_store / device-scope atomic: all of
+// this lane's outstanding memory operations have completed, then a workgroup barrier.
+// After it, one lane may bump the arrival counter.
+__device__ __forceinline__ void publish_complete_and_barrier() {
+  __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
+  lds_barrier();
 }
 
 }  // namespace kvs

@@ -10,8 +10,12 @@
 namespace kvs {
 
 // Work granules of the streaming kernels (units = wave-wide 1 KiB loads).
-constexpr int kPredictUnitsPerWgStep = 4 * 8;  // 4 waves x 8 loads in flight
+constexpr int kPredictUnitsPerWgStep = 16 * 4; // 16 waves x 4 loads in flight
+constexpr int kPredictTargetWgs = 512;         // two 1024-lane workgroups per CU, all resident
 constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs in flight
+constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
+constexpr int kAttnTargetWgs = 1024;           // four 256-lane workgroups per CU
+constexpr int kAttnMaxSplitsPerProblem = 256;  // the merge keeps one weight per split in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
 // call; kvs_workspace_bytes uses the same numbers).
@@ -31,22 +35,26 @@ struct Plan {
   int attn_units;           // wave-loads (of K, and as many of V) per problem
   int attn_units_per_split;
   int attn_splits;          // workgroups per problem
-  // workspace layout (byte offsets, 256-byte aligned)
-  size_t off_gs, off_part_ml, off_part_o, total_bytes;
+  // workspace layout (byte offsets, 256-byte aligned).  The arrival counters at
+  // off_sync must be zero when a call starts; every call leaves them zero.
+  size_t off_sync, sync_bytes, off_hist, off_gs, off_part_ml, off_part_o, total_bytes;
 };
 
 Plan make_plan(const kvs_params& p);
 
 hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void* K,
                                  const float* A, void* K_lr, hipStream_t st);
+// hist == nullptr: scores only.  Otherwise the kernel also adds the histogram of the top
+// 12 key bits of every score to `hist` (kSelectHistBins ints per problem, zero on entry).
 hipError_t launch_predict(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                          const float* A, float* gs, hipStream_t st);
+                          const float* A, float* gs, int* hist, hipStream_t st);
+// hist == nullptr: the selection builds its own histogram.  Otherwise it starts from the
+// finished per-problem histograms and leaves them zeroed.
 hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int32_t* idx,
-                       hipStream_t st);
+                       int* hist, hipStream_t st);
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       hipStream_t st);
-hipError_t launch_combine(const kvs_params& p, const Plan& pl, const float* part_ml,
-                          const float* part_o, void* out, hipStream_t st);
+                       void* out, int* arrivals, hipStream_t st);
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 }  // namespace kvs

@@ -56,8 +56,11 @@ def orc_shape(cfg: Config, n_threads: int = 8, **over) -> oracle.Shape:
 def workspace(p: kv.Params) -> torch.Tensor:
     n = kv.kvs_workspace_bytes(p)
     assert n > 0
-    # poison, so that a kernel relying on zeroed scratch shows up
-    return torch.full((n // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    # poison everything, then let the library prepare its arrival counters: a kernel that
+    # relies on any other part of the scratch being zero shows up as NaN
+    ws = torch.full((n // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    kv.kvs_workspace_init(p, ws)
+    return ws
 
 
 class DeviceLayer:

@@ -79,7 +79,7 @@ def test_check_params(kw, code):
 def test_workspace_covers_scores_and_partials():
     p = _p()
     ws = kv.kvs_workspace_bytes(p)
-    assert ws >= 8 * 8192 * 4 + 8 * 4 * 130 * 4      # group scores + at least one split
+    assert ws >= 8 * 8192 * 4 + 8 * 4 * 130 * 4 + 2 * 8 * 4  # scores, one split, counters
     assert ws % 256 == 0
     assert kv.kvs_workspace_bytes(_p(batch=8)) > ws
 
@@ -108,6 +108,10 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     bad = _p(n_select=9000)._c()
     assert g(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, big, null) == E_SHAPE
     assert f(ctypes.byref(bad), fake, fake, fake, fake, null, fake, big, null) == E_SHAPE
+    w = lib.kvs_workspace_init
+    assert w(ctypes.byref(c), null, big, null) == E_WS
+    assert w(ctypes.byref(c), fake, 8, null) == E_WS
+    assert w(None, fake, big, null) == E_NULL
     h = lib.kvs_build_metadata
     assert h(ctypes.byref(c), null, fake, fake, null) == E_NULL
     assert h(ctypes.byref(c), fake, odd, fake, null) == E_ALIGN
