@@ -10,12 +10,14 @@
 namespace kvs {
 
 // Work granules of the streaming kernels (units = wave-wide 1 KiB loads).
-constexpr int kPredictUnitsPerWgStep = 16 * 4; // 16 waves x 4 loads in flight
-constexpr int kPredictTargetWgs = 512;         // two 1024-lane workgroups per CU, all resident
+constexpr int kPredictWgThreads = 512;
+constexpr int kPredictUnitsPerWgStep = 8 * 8;  // 8 waves x 8 loads in flight
+constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per CU, all resident
 constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs in flight
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
-constexpr int kAttnTargetWgs = 1024;           // four 256-lane workgroups per CU
-constexpr int kAttnMaxSplitsPerProblem = 256;  // the merge keeps one weight per split in LDS
+constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
+constexpr int kAttnMaxSplitsPerProblem = 256;
+constexpr int kAttnMaxGroupsPerWg = 2048;      // selected groups one workgroup stages in LDS  // the merge keeps one weight per split in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
 // call; kvs_workspace_bytes uses the same numbers).

@@ -27,7 +27,7 @@ namespace kvs {
 
 static_assert(kTopkBins == kSelectHistBins, "workspace layout and selection routine disagree");
 
-constexpr int kPredictThreads = kTopkThreads;  // the selection tail wants the full 1024 lanes
+constexpr int kPredictThreads = kPredictWgThreads;
 constexpr int kPredictWaves = kPredictThreads / kWave;
 constexpr int kPredictUnroll = kPredictUnitsPerWgStep / kPredictWaves;  // wave-loads in flight per wave
 static_assert(kPredictUnroll * kPredictWaves == kPredictUnitsPerWgStep, "granule mismatch");
@@ -51,6 +51,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   __shared__ float s_red[kPredictThreads];
   __shared__ float s_qlr[R];
   __shared__ int s_hist[HIST ? kTopkBins : 1];
+  constexpr int kGroupsPerBatch = kGroupInUnit ? U * (RPU / G) : U / UPG;  // per wave
+  __shared__ float s_stage[kPredictWaves][kGroupsPerBatch];  // group scores of a wave's batch
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -65,20 +67,43 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   const int u0 = blockIdx.x * units_per_wg;
   const int u1 = min(units, u0 + units_per_wg);
 
+  // A workgroup step covers kPredictWaves * U consecutive units; wave w takes the U
+  // consecutive units starting at w * U, i.e. one contiguous run of U KiB, whose group
+  // scores are U * RPU / G consecutive floats that leave in one coalesced store.
+  constexpr int kStep = kPredictWaves * U;
+  auto unit_of = [&](int step_base, int j) { return step_base + wave * U + j; };
   uint4 v[U];
   bool ok[U];
-  auto issue = [&](int ub) {
+  auto issue = [&](int step_base) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int row = (ub + u) * RPU + rl;
-      ok[u] = (ub + u < u1) && (row < N);
+      const int unit = unit_of(step_base, u);
+      const int row = unit * RPU + rl;
+      ok[u] = (unit < u1) && (row < N);
       const size_t off = (size_t)(ok[u] ? row : 0) * R + (size_t)c * EPL;
       v[u] = *reinterpret_cast<const uint4*>(Kp + off);
     }
   };
-  // The first batch of K_lr is requested before anything else, so that its latency
-  // overlaps the query projection below.
-  int ub = u0 + wave * U;
+  // Everything the prologue needs from memory is requested up front - the queries, this
+  // lane's entries of the adapter, and the first batch of K_lr - so that the workgroup
+  // pays one memory latency before it streams, not three in a row.
+  constexpr int NSL = kPredictThreads / R;  // slices of the d axis in the projection
+  constexpr int kSpanMax = 128 / NSL;       // adapter rows per lane at d = 128
+  const int pj = tid % R, psl = tid / R;
+  const int span = d / NSL;
+  float qsum_part = 0.f;
+  if (tid < d) {
+    for (int hh = 0; hh < q_per_kv; ++hh)
+      qsum_part += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + tid);
+  }
+  float a_reg[kSpanMax];
+  {
+    const float* Ak = A + (size_t)k * d * R;
+#pragma unroll
+    for (int i = 0; i < kSpanMax; ++i)
+      a_reg[i] = Ak[(size_t)min(psl * span + i, d - 1) * R + pj];  // rows past the span are never used
+  }
+  int ub = u0;  // base of the current workgroup step
   if (ub < u1) issue(ub);
 
   if constexpr (HIST) {  // this workgroup's share of the score histogram
@@ -86,20 +111,13 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   }
 
   // ---- low-rank query vector of this KV head (head-summed) --------------------
-  if (tid < d) {
-    float acc = 0.f;
-    for (int hh = 0; hh < q_per_kv; ++hh)
-      acc += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + tid);
-    s_qsum[tid] = acc;
-  }
+  if (tid < d) s_qsum[tid] = qsum_part;
   lds_barrier();
   {
-    constexpr int NSL = kPredictThreads / R;  // slices of the d axis
-    const int j = tid % R, sl = tid / R;
-    const int span = d / NSL;
-    const float* Ak = A + (size_t)k * d * R;
     float acc = 0.f;
-    for (int i = sl * span; i < (sl + 1) * span; ++i) acc = fmaf(s_qsum[i], Ak[(size_t)i * R + j], acc);
+#pragma unroll
+    for (int i = 0; i < kSpanMax; ++i)
+      if (i < span) acc = fmaf(s_qsum[psl * span + i], a_reg[i], acc);
     s_red[tid] = acc;
     lds_barrier();
     if (tid < R) {
@@ -126,16 +144,17 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
       for (int e = 0; e < EPL; ++e) acc = fmaf(qr[e], f[e], acc);
       sc[u] = allreduce_lanes<OpSum, 1, LPR>(acc);  // token score, on all LPR lanes of the row
     }
+    // Group representatives go through a per-wave LDS line so that they leave as one
+    // coalesced store per batch (scattered 4-byte stores per unit cost ~8 % of the
+    // streaming bandwidth).  Only this wave touches its line, in program order.
     if constexpr (kGroupInUnit) {
+      constexpr int GPU_ = RPU / G;  // groups per unit
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float g;
         if (mean) g = allreduce_lanes<OpSum, LPR, LPR * G>(sc[u]) * inv_g;
         else g = allreduce_lanes<OpMax, LPR, LPR * G>(sc[u]);
-        if (ok[u] && (lane % (LPR * G)) == 0) {
-          gsp[((ub + u) * RPU + rl) / G] = g;
-          if constexpr (HIST) atomicAdd(&s_hist[score_key(g) >> kTopkLowBits], 1);
-        }
+        if ((lane % (LPR * G)) == 0) s_stage[wave][u * GPU_ + lane / (LPR * G)] = g;
       }
     } else {
 #pragma unroll
@@ -145,13 +164,25 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
         for (int t = 1; t < UPG; ++t) g = mean ? g + sc[u0g + t] : fmaxf(g, sc[u0g + t]);
         if (mean) g = allreduce_lanes<OpSum, LPR, kWave>(g) * inv_g;
         else g = allreduce_lanes<OpMax, LPR, kWave>(g);
-        if (ok[u0g] && lane == 0) {
-          gsp[((ub + u0g) * RPU) / G] = g;
+        if (lane == 0) s_stage[wave][u0g / UPG] = g;
+      }
+    }
+    {
+      // first group of this wave's batch; groups never straddle units' ends, so a group is
+      // valid iff its first row is
+      const int row0 = unit_of(ub, 0) * RPU;
+      const int grp0 = row0 / G;
+      const int row_end = min(N, u1 * RPU);
+#pragma unroll
+      for (int t = lane; t < kGroupsPerBatch; t += kWave) {
+        if ((grp0 + t) * G < row_end) {
+          const float g = s_stage[wave][t];
+          gsp[grp0 + t] = g;
           if constexpr (HIST) atomicAdd(&s_hist[score_key(g) >> kTopkLowBits], 1);
         }
       }
     }
-    ub += kPredictWaves * U;
+    ub += kStep;
     if (ub < u1) issue(ub);
   }
 

@@ -311,7 +311,10 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
       for (int j = c0; j < c0 + kTopkChunk; ++j) {
         if (j < kpt && first + j < NG) {
           const bool gt = key[j] > T, eq = key[j] == T;
-          if (gt || (eq && eq_before < need)) out[gt_before + min(eq_before, need)] = first + j;
+          // (the bound only matters if the caller handed in a histogram that does not
+          // belong to these scores, e.g. a workspace that was never initialised)
+          const int pos = gt_before + min(eq_before, need);
+          if ((gt || (eq && eq_before < need)) && pos < M) out[pos] = first + j;
           gt_before += gt ? 1 : 0;
           eq_before += eq ? 1 : 0;
         }
