@@ -44,8 +44,7 @@ def algorithmic_bytes(cfg) -> dict:
     predict = P * cfg.ctx_len * cfg.rank * eb + q_bytes + a_bytes + P * NG * 4
     topk = P * NG * 4 + P * M * 4
     attn = P * M * 4 + 2 * P * M * cfg.group_size * cfg.head_dim * eb + q_bytes + q_bytes
-    return {"predict": predict, "topk": topk, "predict_select": predict + topk, "attn": attn,
-            "step": predict + topk + attn}
+    return {"predict": predict, "topk": topk, "attn": attn, "step": predict + topk + attn}
 
 
 # --------------------------------------------------------------------------------------
@@ -160,32 +159,45 @@ def time_steps(wl: Workload, steps: int, warmup: int, mode: str) -> float:
 
 
 def time_kernels(wl: Workload, reps: int) -> dict:
-    """Average duration of each kernel family, from HIP events on the launch stream:
-    `reps` back-to-back launches over the rotating copies between two events (so the
-    figure includes the gap between consecutive launches and is an upper bound on the
-    kernel's own duration)."""
+    """Average duration of each of the step's three kernels, from HIP events recorded on
+    the launch stream around every single launch of `reps` steps over the rotating copies
+    (the step is issued through the split entry points, which launch the same kernels as
+    kvs_decode_step).  An event pair adds about a microsecond to a very short kernel; the
+    rocprofv3 kernel trace under profiles/ has the kernels' own durations."""
     torch, kv, p = wl.torch, wl.kv, wl.p
+    names = ("predict", "topk", "attn")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
 
-    def timed(fn):
-        for i in range(min(reps, 2 * len(wl.slots))):
-            fn(wl.slots[i % len(wl.slots)])
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(reps):
-            fn(wl.slots[i % len(wl.slots)])
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps   # us
+    def one(s, e):
+        e[0].record()
+        kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"], wl.ws)
+        e[1].record()
+        kv.kvs_select_topk(p, s["gs"], s["idx"], wl.ws)
+        e[2].record()
+        kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], wl.ws)
+        e[3].record()
 
+    for i in range(min(reps, len(wl.slots))):
+        one(wl.slots[i % len(wl.slots)], ev[0])
+    torch.cuda.synchronize()
+    for i in range(reps):
+        one(wl.slots[i % len(wl.slots)], ev[i])
+    torch.cuda.synchronize()
     out = {}
-    # the two launches of a step ...
-    out["predict_select"] = timed(lambda s: kv.kvs_predict_select(p, s["q"], s["K_lr"], s["A"], s["idx"], None, wl.ws))
-    out["attn"] = timed(lambda s: kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], wl.ws))
-    # ... and, for reference, the streaming part of the first one without the selection tail
-    out["predict_scores_only"] = timed(lambda s: kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"]))
-    out["topk_only"] = timed(lambda s: kv.kvs_select_topk(p, s["gs"], s["idx"]))
+    for j, n in enumerate(names):
+        out[n] = sum(e[j].elapsed_time(e[j + 1]) for e in ev) * 1e3 / reps   # us
     return out
+
+
+def load_traffic(cfg_name: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled
+    by a plain copy of known size), if a summary for this workload has been committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[cfg_name][kernel]["bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
@@ -234,7 +246,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> 
     one.__dict__.update(wl.__dict__)
     one.slots = wl.slots[:1] if layers == 1 else wl.slots
     warm_ms = time_steps(one, steps, warmup, mode) / steps * 1e3 if layers == 1 else None
-    dom = max(("predict_select", "attn"), key=lambda k: kern[k])
+    dom = max(("predict", "attn"), key=lambda k: kern[k])
     achieved = ab[dom] / (kern[dom] * 1e-6) / 1e9
     res = {
         "tokens_per_s": cfg.batch / (ms_step * 1e-3),
@@ -244,7 +256,8 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> 
         "kernel_us": kern,
         "dominant": dom,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": load_traffic(cfg.name, dom),
                      "algorithmic_bytes": ab[dom], "kernel_us": kern[dom]},
         "algorithmic_bytes": ab,
         "copies": len(wl.slots),
@@ -268,6 +281,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=None, help="rotating input copies (default: 3x the caches)")
     ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run one 256 MiB device copy (calibration kernel for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -283,6 +298,14 @@ def main() -> int:
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
     import paper_2511_11907_amd as kv
     log(f"[bench] {kv.kvs_version()} from {kv.library_path()} on {torch.cuda.get_device_name(0)}")
+
+    if args.pmc_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = PRESETS[args.config]
     main_res = measure(cfg, args.steps, args.warmup, args.mode, args.copies, log,

@@ -112,13 +112,18 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
                               const float* A, int32_t* idx, float* group_scores,
                               void* workspace, size_t workspace_bytes, void* stream);
 
-/* The two halves of kvs_predict_select as separate launches (same arithmetic, same
- * device routines): kvs_predict_scores writes group_scores [B,H_kv,N/G] (required
- * here), kvs_select_topk reads them and writes idx.  Neither needs a workspace. */
+/* The two launches of kvs_predict_select as separate calls (same kernels).
+ * kvs_predict_scores writes group_scores [B,H_kv,N/G] (required here);
+ * kvs_select_topk reads them and writes idx.  workspace may be NULL in both: the
+ * selection then builds its own score histogram.  If kvs_predict_scores is given a
+ * workspace it also leaves the per-problem score histograms there, and the NEXT call
+ * on that workspace must be kvs_select_topk with the same workspace and params (it
+ * consumes the histograms and zeroes them again). */
 kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr,
-                              const float* A, float* group_scores, void* stream);
+                              const float* A, float* group_scores, void* workspace,
+                              size_t workspace_bytes, void* stream);
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
-                           void* stream);
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* Sec. 4.4 (attention consumes only the selected KV groups): softmax attention
  * of every query head over the G*M tokens named by idx of its KV head, gathered

@@ -98,9 +98,9 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_build_metadata.restype = ctypes.c_int
     lib.kvs_predict_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_predict_select.restype = ctypes.c_int
-    lib.kvs_predict_scores.argtypes = [pp, vp, vp, vp, vp, vp]
+    lib.kvs_predict_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_predict_scores.restype = ctypes.c_int
-    lib.kvs_select_topk.argtypes = [pp, vp, vp, vp]
+    lib.kvs_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.kvs_select_topk.restype = ctypes.c_int
     lib.kvs_sparse_decode_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_sparse_decode_attn.restype = ctypes.c_int
@@ -220,28 +220,30 @@ def kvs_predict_select(p: Params, q, K_lr, A, idx, group_scores, workspace, stre
     _check(st, "kvs_predict_select")
 
 
-def kvs_predict_scores(p: Params, q, K_lr, A, group_scores, stream=None) -> None:
+def kvs_predict_scores(p: Params, q, K_lr, A, group_scores, workspace=None, stream=None) -> None:
     torch = _torch()
     kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
     c = p._c()
+    ws, nws = _ws(workspace)
     st = load_library().kvs_predict_scores(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
         _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
         _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
-        _stream(stream))
+        ws, nws, _stream(stream))
     _check(st, "kvs_predict_scores")
 
 
-def kvs_select_topk(p: Params, group_scores, idx, stream=None) -> None:
+def kvs_select_topk(p: Params, group_scores, idx, workspace=None, stream=None) -> None:
     torch = _torch()
     c = p._c()
+    ws, nws = _ws(workspace)
     st = load_library().kvs_select_topk(
         ctypes.byref(c),
         _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
         _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
-        _stream(stream))
+        ws, nws, _stream(stream))
     _check(st, "kvs_select_topk")
 
 

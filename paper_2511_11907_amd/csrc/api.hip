@@ -188,24 +188,35 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
 }
 
 kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr, const float* A,
-                              float* group_scores, void* stream) {
+                              float* group_scores, void* workspace, size_t workspace_bytes,
+                              void* stream) {
   if (!p || !q || !K_lr || !A || !group_scores) return KVS_ERR_NULL;
-  const kvs_status s = check_params(p, true);
+  kvs_status s = check_params(p, true);
   if (s != KVS_OK) return s;
   if (misaligned(q) || misaligned(K_lr) || misaligned(A) || misaligned(group_scores))
     return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
-  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, nullptr, (hipStream_t)stream));
+  int* hist = nullptr;
+  if (workspace) {
+    if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+    hist = (int*)((char*)workspace + pl.off_hist);
+  }
+  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, hist, (hipStream_t)stream));
 }
 
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
-                           void* stream) {
+                           void* workspace, size_t workspace_bytes, void* stream) {
   if (!p || !group_scores || !idx) return KVS_ERR_NULL;
-  const kvs_status s = check_params(p, true);
+  kvs_status s = check_params(p, true);
   if (s != KVS_OK) return s;
   if (misaligned(group_scores) || misaligned(idx)) return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
-  return dev(launch_topk(*p, pl, group_scores, idx, nullptr, (hipStream_t)stream));
+  int* hist = nullptr;
+  if (workspace) {
+    if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+    hist = (int*)((char*)workspace + pl.off_hist);
+  }
+  return dev(launch_topk(*p, pl, group_scores, idx, hist, (hipStream_t)stream));
 }
 
 kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,

@@ -209,6 +209,84 @@ def test_runs_on_a_side_stream():
     assert H.attn_error(H.out_values(out), out_ref) <= H.ATTN_TOL["bf16"]
 
 
+def test_split_calls_match_the_fused_calls_and_steps_repeat_bit_exactly():
+    """(a) predict_scores + select_topk (with and without the histogram hand-off) and the
+    one-call forms give identical indices; (b) many steps that share one workspace, over
+    rotating inputs, reproduce each input's first result bit for bit - a stale read of
+    another workgroup's partial result or a counter left dirty would break this."""
+    cfg = SCALED["c2_small"].replace(batch=2, ctx_len=8192, n_select=205)
+    p = H.kv_params(cfg)
+    sh = H.orc_shape(cfg)
+    ws = H.workspace(p)
+    copies = []
+    for c in range(3):
+        L = make_layer(cfg, seq_offset=c * cfg.batch)
+        klr = oracle.build_metadata(sh, L.K, L.A)
+        D = H.DeviceLayer(L)
+        copies.append((L, D, H.to_dev(klr), klr))
+    B, Hk, M = cfg.batch, cfg.n_kv_heads, cfg.n_select
+
+    def bufs():
+        return (torch.full((B, Hk, M), -1, dtype=torch.int32, device=H.DEV),
+                torch.full((B, Hk, cfg.n_groups), float("nan"), dtype=torch.float32, device=H.DEV),
+                torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.bfloat16, device=H.DEV))
+
+    first = []
+    for (L, D, klr_d, klr) in copies:
+        idx, gs, out = bufs()
+        kv.kvs_decode_step(p, D.q, klr_d, D.A, D.K, D.V, idx, gs, out, ws)
+        torch.cuda.synchronize()
+        ref = oracle.predict_select(sh, L.q, klr, L.A)
+        np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+        first.append((idx.cpu().numpy(), H.to_host_storage(out)))
+        # split calls, histogram handed over through the workspace
+        idx2, gs2, _ = bufs()
+        kv.kvs_predict_scores(p, D.q, klr_d, D.A, gs2, ws)
+        kv.kvs_select_topk(p, gs2, idx2, ws)
+        # split calls, selection on its own
+        idx3, gs3, _ = bufs()
+        kv.kvs_predict_scores(p, D.q, klr_d, D.A, gs3)
+        kv.kvs_select_topk(p, gs3, idx3)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(idx2.cpu().numpy(), first[-1][0])
+        np.testing.assert_array_equal(idx3.cpu().numpy(), first[-1][0])
+        np.testing.assert_array_equal(gs2.cpu().numpy(), gs.cpu().numpy())
+    idx, gs, out = bufs()
+    for step in range(60):
+        c = step % 3
+        L, D, klr_d, klr = copies[c]
+        kv.kvs_decode_step(p, D.q, klr_d, D.A, D.K, D.V, idx, None, out, ws)
+        if step % 7 == 0 or step >= 54:
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(idx.cpu().numpy(), first[c][0])
+            np.testing.assert_array_equal(H.to_host_storage(out), first[c][1])
+    torch.cuda.synchronize()
+
+
+def test_uninitialised_histogram_cannot_write_out_of_bounds():
+    """A workspace whose counter area was never zeroed gives wrong selections, but the
+    selection kernel must stay inside idx: a guard row after idx has to survive."""
+    cfg = SCALED["c5_small"]
+    L = make_layer(cfg)
+    D = H.DeviceLayer(L)
+    p = H.kv_params(cfg)
+    sh = H.orc_shape(cfg)
+    klr_d = H.to_dev(oracle.build_metadata(sh, L.K, L.A))
+    n = kv.kvs_workspace_bytes(p)
+    ws = torch.full((n // 4,), 1.0e9, dtype=torch.float32, device=H.DEV).view(torch.int32)
+    ws.fill_(977)                      # junk counters instead of zeros
+    B, Hk, M = cfg.batch, cfg.n_kv_heads, cfg.n_select
+    buf = torch.full((B * Hk * M + 4096,), -7, dtype=torch.int32, device=H.DEV)
+    idx = buf[: B * Hk * M].view(B, Hk, M)
+    gs = torch.empty((B, Hk, cfg.n_groups), dtype=torch.float32, device=H.DEV)
+    kv.kvs_predict_scores(p, D.q, klr_d, D.A, gs, ws)
+    kv.kvs_select_topk(p, gs, idx, ws)
+    torch.cuda.synchronize()
+    assert bool((buf[B * Hk * M:] == -7).all())
+    got = idx.cpu().numpy()
+    assert got.max() < cfg.n_groups     # whatever was written is a group index
+
+
 # ---- full-size configurations, oracle on sampled problems ------------------------------------------
 def _full_size_sampled(cfg: Config, samples, budgets=None, layer=0):
     """GPU on the whole batch at the real size; oracle on the sampled (b, k) problems.
