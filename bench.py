@@ -159,33 +159,38 @@ def time_steps(wl: Workload, steps: int, warmup: int, mode: str) -> float:
 
 
 def time_kernels(wl: Workload, reps: int) -> dict:
-    """Average duration of each of the step's three kernels, from HIP events recorded on
-    the launch stream around every single launch of `reps` steps over the rotating copies
-    (the step is issued through the split entry points, which launch the same kernels as
-    kvs_decode_step).  An event pair adds about a microsecond to a very short kernel; the
-    rocprofv3 kernel trace under profiles/ has the kernels' own durations."""
+    """Average duration of each of the step's three kernels from HIP events on the launch
+    stream: `reps` back-to-back launches over the rotating copies between two events, through
+    the split entry points (the same kernels kvs_decode_step launches).  The figure includes
+    the gap between consecutive launches (about a microsecond), so it is an upper bound on
+    the kernel's own duration; the rocprofv3 kernel trace under profiles/ has the latter.
+    The selection kernel consumes the histogram the prediction kernel leaves behind, so it
+    is timed as (prediction + selection) minus prediction."""
     torch, kv, p = wl.torch, wl.kv, wl.p
-    names = ("predict", "topk", "attn")
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
 
-    def one(s, e):
-        e[0].record()
+    def timed(fn):
+        for i in range(min(reps, len(wl.slots))):
+            fn(wl.slots[i % len(wl.slots)])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(wl.slots[i % len(wl.slots)])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps   # us
+
+    def pair(s):
         kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"], wl.ws)
-        e[1].record()
         kv.kvs_select_topk(p, s["gs"], s["idx"], wl.ws)
-        e[2].record()
-        kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], wl.ws)
-        e[3].record()
 
-    for i in range(min(reps, len(wl.slots))):
-        one(wl.slots[i % len(wl.slots)], ev[0])
-    torch.cuda.synchronize()
-    for i in range(reps):
-        one(wl.slots[i % len(wl.slots)], ev[i])
-    torch.cuda.synchronize()
     out = {}
-    for j, n in enumerate(names):
-        out[n] = sum(e[j].elapsed_time(e[j + 1]) for e in ev) * 1e3 / reps   # us
+    both = timed(pair)
+    # prediction alone keeps adding to the histograms; reset them afterwards
+    out["predict"] = timed(lambda s: kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"], wl.ws))
+    kv.kvs_workspace_init(p, wl.ws)
+    out["topk"] = max(both - out["predict"], 0.0)
+    out["attn"] = timed(lambda s: kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], wl.ws))
     return out
 
 
