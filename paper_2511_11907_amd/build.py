@@ -38,6 +38,10 @@ def build(jobs: int = 5) -> str:
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    # A shared object links even with unresolved kernel stubs; loading it is what tells.
+    # (In a child process: loading here would pull in the system HIP runtime ahead of the
+    # one torch brings along.)
+    subprocess.run([sys.executable, "-c", f"import ctypes; ctypes.CDLL({LIB!r})"], check=True)
     return LIB
 
 

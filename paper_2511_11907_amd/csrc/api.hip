@@ -62,9 +62,6 @@ Plan make_plan(const kvs_params& p) {
     const int want = ceil_div(target("KVS_ATTN_WGS", kAttnTargetWgs), pl.problems);
     const int most = ceil_div(pl.attn_units, kAttnUnitsPerWgStep);
     int splits = want < 1 ? 1 : (want > most ? most : want);
-    // a workgroup stages the indices of its groups in LDS: bound the groups per split
-    const int least = ceil_div(p.n_select, kAttnMaxGroupsPerWg - 2);
-    if (splits < least) splits = least;
     if (splits > kAttnMaxSplitsPerProblem) splits = kAttnMaxSplitsPerProblem;
     pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWgStep);
     pl.attn_splits = ceil_div(pl.attn_units, pl.attn_units_per_split);

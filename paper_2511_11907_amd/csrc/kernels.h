@@ -17,7 +17,7 @@ constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs i
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;
-constexpr int kAttnMaxGroupsPerWg = 2048;      // selected groups one workgroup stages in LDS  // the merge keeps one weight per split in LDS
+constexpr int kAttnMaxGroupsPerWg = 512;       // selected groups one workgroup stages in LDS  // the merge keeps one weight per split in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
 // call; kvs_workspace_bytes uses the same numbers).
