@@ -92,6 +92,9 @@ class Workload:
             s["idx"] = torch.empty((B, Hk, cfg.n_select), dtype=torch.int32, device=dev)
             s["gs"] = torch.empty((B, Hk, cfg.n_groups), dtype=torch.float32, device=dev)
             s["out"] = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=tdt, device=dev)
+            # a workspace of its own, so that layer-steps in flight together do not share one
+            s["ws"] = torch.empty_like(self.ws)
+            kv.kvs_workspace_init(self.p, s["ws"])
             self.slots.append(s)
             if c == 0:
                 self.host0 = L
@@ -113,34 +116,73 @@ class Workload:
             for l in range(self.layers_per_step):
                 self.layer_step(l)
 
+    def run(self, count: int, layer_ahead: bool = False):
+        """`count` steps on the current stream.  With `layer_ahead`, the layer-steps are
+        issued the way the method's runtime pipelines them (Sec. 3.3, 3.4: the groups of
+        layer i are predicted while layer i-1 is still computing, from a query known one
+        layer early): prediction, selection and attention each on a stream of their own,
+        chained per layer by events, so the prediction of the following layers overlaps
+        the selection and attention of this one.  Forks from and joins the current stream,
+        so the whole thing can be captured into a graph."""
+        if not layer_ahead:
+            for i in range(count):
+                self.step(i)
+            return
+        torch, kv, p = self.torch, self.kv, self.p
+        main = torch.cuda.current_stream()
+        if not hasattr(self, "side"):
+            self.side = (torch.cuda.Stream(), torch.cuda.Stream())
+        s_sel, s_att = self.side
+        s_sel.wait_stream(main)
+        s_att.wait_stream(main)
+        n = count * self.layers_per_step
+        last = {}                                       # slot -> event of its last attention
+        for j in range(n):
+            k = j % len(self.slots)
+            s = self.slots[k]
+            if k in last:                               # the slot's buffers are reused
+                main.wait_event(last[k])
+            kv.kvs_predict_scores(p, s["q"], s["K_lr"], s["A"], s["gs"], s["ws"])
+            e_p = torch.cuda.Event()
+            e_p.record(main)
+            with torch.cuda.stream(s_sel):
+                s_sel.wait_event(e_p)
+                kv.kvs_select_topk(p, s["gs"], s["idx"], s["ws"])
+                e_t = torch.cuda.Event()
+                e_t.record(s_sel)
+            with torch.cuda.stream(s_att):
+                s_att.wait_event(e_t)
+                kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], s["ws"])
+                e_a = torch.cuda.Event()
+                e_a.record(s_att)
+            last[k] = e_a
+        main.wait_stream(s_sel)
+        main.wait_stream(s_att)
 
-def time_steps(wl: Workload, steps: int, warmup: int, mode: str) -> float:
+
+def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bool = False) -> float:
     """Seconds for exactly `steps` steps (after `warmup` untimed ones)."""
     torch = wl.torch
     n = len(wl.slots) if wl.layers_per_step == 1 else 1   # steps per rotation
     if mode == "eager":
-        for i in range(warmup):
-            wl.step(i)
+        wl.run(warmup, layer_ahead)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(steps):
-            wl.step(i)
+        wl.run(steps, layer_ahead)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
     # graph mode: one captured rotation (n steps), plus a tail graph if steps % n != 0
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        for i in range(max(2, min(warmup, n))):
-            wl.step(i)
+        wl.run(max(2, min(warmup, n)), layer_ahead)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
 
     def capture(count):
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for i in range(count):
-                wl.step(i)
+            wl.run(count, layer_ahead)
         return g
 
     full, tail = divmod(steps, n)
@@ -251,6 +293,10 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> 
     one.__dict__.update(wl.__dict__)
     one.slots = wl.slots[:1] if layers == 1 else wl.slots
     warm_ms = time_steps(one, steps, warmup, mode) / steps * 1e3 if layers == 1 else None
+    # the same steps issued layer-ahead (prediction of later layers overlapping the
+    # selection and attention of earlier ones); with a one-layer workload the rotating
+    # copies stand in for the successive layers of a model
+    ahead_ms = time_steps(wl, steps, warmup, mode, layer_ahead=True) / steps * 1e3
     dom = max(("predict", "attn"), key=lambda k: kern[k])
     achieved = ab[dom] / (kern[dom] * 1e-6) / 1e9
     res = {
@@ -267,6 +313,8 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> 
         "algorithmic_bytes": ab,
         "copies": len(wl.slots),
         "warm_ms_per_step": warm_ms,
+        "layer_ahead": {"us_per_layer": ahead_ms * 1e3 / layers,
+                        "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if want_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, wl.host0)
@@ -321,7 +369,7 @@ def main() -> int:
         st = max(20, min(args.steps, 60))
         r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False)
         others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
-                                          "roofline", "copies")}
+                                          "roofline", "copies", "layer_ahead")}
         others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
 
     line = {
@@ -345,6 +393,7 @@ def main() -> int:
         "step_hbm_gbps": main_res["step_gbps"],
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
         "warm_ms_per_step": main_res["warm_ms_per_step"],
+        "layer_ahead": main_res["layer_ahead"],
         "kernel_us": main_res["kernel_us"],
         "algorithmic_bytes": main_res["algorithmic_bytes"],
         "roofline": main_res["roofline"],
