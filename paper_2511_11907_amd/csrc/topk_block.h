@@ -1,6 +1,5 @@
-// Workgroup-level top-M selection (Sec. 4.3, "TopK"), used both as a kernel of its own
-// and as the tail of the prediction kernel: the indices of the M largest fp32 scores of
-// one problem, ties to the lower index, written in ascending index order.
+// Workgroup-level top-M selection (Sec. 4.3, "TopK"): the indices of the M largest fp32
+// scores of one problem, ties to the lower index, written in ascending index order.
 //
 // Scores are compared as order-preserving 32-bit keys.  The key T of the M-th largest
 // score is found MSB-first:
