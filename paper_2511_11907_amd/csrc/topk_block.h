@@ -107,7 +107,8 @@ __device__ __forceinline__ bool descend(TopkShared& sh, int round, int c1, int c
 }
 
 // All kTopkThreads lanes of the workgroup must call this with the same arguments.
-// g: NG scores; out: M indices; 1 <= M <= NG <= kTopkThreads * kTopkMaxPerLane.
+// g: NG scores (16-byte aligned if NG is a multiple of 4); out: M indices;
+// 1 <= M <= NG <= kTopkThreads * kTopkMaxPerLane.
 // hist_global: nullptr => the histogram of the top 12 key bits is built here, in LDS;
 // otherwise it points at the problem's kTopkBins counters in global memory, completed
 // by an earlier kernel, and they are reset to zero on the way.
@@ -123,7 +124,12 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     for (int c = 0; c < kTopkBinsPerLane; ++c)
       mine[c] = hist_global[kTopkBins - 1 - (tid * kTopkBinsPerLane + c)];
   }
-  const int kpt = (NG + kTopkThreads - 1) / kTopkThreads;  // scores per lane
+  // A lane owns a contiguous slice of kpt scores (what the ordered compaction needs).
+  // With NG a multiple of four the slice is a whole number of 16-byte pieces and is
+  // fetched as such: a wave then touches a few cache lines per load instead of 64.
+  const bool vec = (NG & 3) == 0;  // uniform
+  int kpt = (NG + kTopkThreads - 1) / kTopkThreads;  // scores per lane
+  if (vec) kpt = (kpt + 3) & ~3;
   const int first = tid * kpt;
 
   // Slice of this lane, as keys, fetched in chunks of kTopkChunk slots whose loads are
@@ -131,18 +137,35 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
   // Slots beyond the slice (and beyond NG) hold key 0, which is below the key of every
   // finite score.
   uint32_t key[kTopkMaxPerLane];
+  {
+    // every chunk's loads are requested before the first value is looked at, so a long
+    // slice still costs one memory latency
+    float x[kTopkMaxPerLane];
 #pragma unroll
-  for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-    if (c0 < kpt) {  // uniform
-      float x[kTopkChunk];
+    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
+      if (c0 < kpt && vec) {  // uniform
 #pragma unroll
-      for (int j = 0; j < kTopkChunk; ++j) x[j] = g[min(first + c0 + j, NG - 1)];
+        for (int j = c0; j < c0 + kTopkChunk; j += 4) {
+          const float4 v = *reinterpret_cast<const float4*>(g + min(first + j, NG - 4));
+          x[j] = v.x, x[j + 1] = v.y, x[j + 2] = v.z, x[j + 3] = v.w;
+        }
+      } else if (c0 < kpt) {  // uniform
 #pragma unroll
-      for (int j = 0; j < kTopkChunk; ++j)
-        key[c0 + j] = (c0 + j < kpt && first + c0 + j < NG) ? score_key(x[j]) : 0u;
-    } else {
+        for (int j = c0; j < c0 + kTopkChunk; ++j) x[j] = g[min(first + j, NG - 1)];
+      } else {
 #pragma unroll
-      for (int j = 0; j < kTopkChunk; ++j) key[c0 + j] = 0u;
+        for (int j = c0; j < c0 + kTopkChunk; ++j) x[j] = 0.f;
+      }
+    }
+    // (pins every request above the first use: without it the compiler pairs each chunk's
+    // loads with its conversions and waits chunk by chunk)
+#pragma unroll
+    for (int j = 0; j < kTopkMaxPerLane; ++j) asm volatile("" : "+v"(x[j]));
+#pragma unroll
+    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
+#pragma unroll
+      for (int j = c0; j < c0 + kTopkChunk; ++j)
+        key[j] = (c0 < kpt && j < kpt && first + j < NG) ? score_key(x[j]) : 0u;
     }
   }
 
