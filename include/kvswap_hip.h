@@ -3,12 +3,12 @@
  * hand-written HIP kernels for gfx950 (MI355X), behind a plain C ABI.
  *
  * One decode step of one layer, per (sequence b, KV head k) problem:
- *   predict : s[n] = sum_{h: g(h)=k} (q[h] . A[k]) . K_lr[n]       (Sec. 4.3, Eq. 1)
+ *   predict : s[n] = sum_{h: g(h)=k} (q[h] . A[k]) . K_lr[n]       (Sec. 3.3, Eq. 1)
  *   group   : gs[j] = max (or mean) of s over the G tokens of group j
  *   select  : idx = the M groups with the largest gs               (ReduceMax + TopK)
  *   attend  : out[h] = softmax(scale * q[h] . K[sel]^T) . V[sel]    over the selected
- *             groups' tokens only                                   (Sec. 4.4, KV cache manager)
- * with the compact metadata K_lr = K . A built once per token (Sec. 4.2).
+ *             groups' tokens only                                   (Sec. 3.4, KV cache manager)
+ * with the compact metadata K_lr = K . A built once per token (Sec. 3.2).
  * The paper adopts one joint adapter for all KV heads; this library implements
  * its per-head design (a): one adapter A[k] (d x r), one K_lr and one selection
  * per KV head.  The full K/V cache lives in device memory (it stands in for the
@@ -96,13 +96,13 @@ kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t works
  * calls would return for them. */
 kvs_status kvs_check_params(const kvs_params* p);
 
-/* Sec. 4.2: K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32 accumulation, one rounding
+/* Sec. 3.2: K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32 accumulation, one rounding
  * (nearest-even) to meta_dtype.  Run at prefill and whenever new groups are
  * appended; not part of the per-step latency.  n_select is ignored. */
 kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A,
                               void* K_lr, void* stream);
 
-/* Sec. 4.3 (Eq. 1, "Scoring and selection"): low-rank token scores summed over
+/* Sec. 3.3 (Eq. 1, "Scoring and selection"): low-rank token scores summed over
  * the query heads of each KV head, group representative (max or mean), and the
  * indices of the M best groups per (b, kv head): ties go to the lower index,
  * output ascending.  Two launches: the streaming kernel also histograms the
@@ -125,7 +125,7 @@ kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
                            void* workspace, size_t workspace_bytes, void* stream);
 
-/* Sec. 4.4 (attention consumes only the selected KV groups): softmax attention
+/* Sec. 3.4 (attention consumes only the selected KV groups): softmax attention
  * of every query head over the G*M tokens named by idx of its KV head, gathered
  * from the full K/V, fp32 online softmax, result rounded to kv_dtype.  One
  * launch (split over the selected groups, merged by the last workgroup). */

@@ -17,6 +17,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 REDUCE_MAX, REDUCE_MEAN = 0, 1
+HEADS_SEPARATE, HEADS_JOINT = 0, 1
 
 
 class _Params(ctypes.Structure):
@@ -25,7 +26,7 @@ class _Params(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32),
-        ("reduce", ctypes.c_int32), ("n_threads", ctypes.c_int32),
+        ("reduce", ctypes.c_int32), ("head_mode", ctypes.c_int32), ("n_threads", ctypes.c_int32),
         ("softmax_scale", ctypes.c_double),
     ]
 
@@ -45,15 +46,22 @@ class Shape:
     reduce: int = REDUCE_MAX
     n_threads: int = 1
     softmax_scale: float = 0.0
+    head_mode: int = HEADS_SEPARATE
 
     def _c(self) -> _Params:
         return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                        self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
-                       self.meta_dtype, self.reduce, self.n_threads, self.softmax_scale)
+                       self.meta_dtype, self.reduce, self.head_mode, self.n_threads,
+                       self.softmax_scale)
 
     @property
     def n_groups(self) -> int:
         return self.ctx_len // self.group_size
+
+    @property
+    def sets(self) -> tuple:
+        """Leading axes of the per-selection-set tensors (K_lr, idx, gs, s)."""
+        return (self.batch,) if self.head_mode == HEADS_JOINT else (self.batch, self.n_kv_heads)
 
 
 _lib = None
@@ -103,10 +111,10 @@ def _check(rc, what):
 
 def build_metadata(sh: Shape, K, A, want_exact: bool = False):
     """K_lr = K . A, rounded once to meta_dtype.  Returns storage array
-    [B,H_kv,N,r] (and the unrounded fp64 products if want_exact)."""
+    [B,H_kv,N,r] ([B,N,r] in joint mode) (and the unrounded fp64 products if want_exact)."""
     K = _arr(K, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.head_dim), "K")
     A = _arr(A, np.float32, (sh.n_kv_heads, sh.head_dim, sh.rank), "A")
-    out = np.empty((sh.batch, sh.n_kv_heads, sh.ctx_len, sh.rank), dtype=_np_dtype(sh.meta_dtype))
+    out = np.empty(sh.sets + (sh.ctx_len, sh.rank), dtype=_np_dtype(sh.meta_dtype))
     exact = np.empty(out.shape, dtype=np.float64) if want_exact else None
     c = sh._c()
     _check(lib().oracle_build_metadata(ctypes.byref(c), _ptr(K), _ptr(A), _ptr(out), _ptr(exact)),
@@ -116,11 +124,11 @@ def build_metadata(sh: Shape, K, A, want_exact: bool = False):
 
 def predict_select(sh: Shape, q, K_lr, A):
     """Returns dict(idx [B,H_kv,M] int32 ascending, gs [B,H_kv,NG] f64,
-    s [B,H_kv,N] f64, boundary [B,H_kv,2] f64)."""
+    s [B,H_kv,N] f64, boundary [B,H_kv,2] f64); no H_kv axis in joint mode."""
     q = _arr(q, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_q_heads, sh.head_dim), "q")
-    K_lr = _arr(K_lr, _np_dtype(sh.meta_dtype), (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.rank), "K_lr")
+    K_lr = _arr(K_lr, _np_dtype(sh.meta_dtype), sh.sets + (sh.ctx_len, sh.rank), "K_lr")
     A = _arr(A, np.float32, (sh.n_kv_heads, sh.head_dim, sh.rank), "A")
-    P = (sh.batch, sh.n_kv_heads)
+    P = sh.sets
     idx = np.empty(P + (sh.n_select,), dtype=np.int32)
     gs = np.empty(P + (sh.n_groups,), dtype=np.float64)
     s = np.empty(P + (sh.ctx_len,), dtype=np.float64)
@@ -136,7 +144,7 @@ def sparse_attn(sh: Shape, q, K, V, idx):
     shape_kv = (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.head_dim)
     K = _arr(K, _np_dtype(sh.kv_dtype), shape_kv, "K")
     V = _arr(V, _np_dtype(sh.kv_dtype), shape_kv, "V")
-    idx = _arr(idx, np.int32, (sh.batch, sh.n_kv_heads, sh.n_select), "idx")
+    idx = _arr(idx, np.int32, sh.sets + (sh.n_select,), "idx")
     out = np.empty((sh.batch, sh.n_q_heads, sh.head_dim), dtype=np.float64)
     c = sh._c()
     _check(lib().oracle_sparse_attn(ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(out)),

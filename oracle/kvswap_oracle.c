@@ -56,14 +56,40 @@ static int params_ok(const orc_params* p) {
   if (p->ctx_len % p->group_size) return 0;
   if (p->kv_dtype != ORC_F32 && p->kv_dtype != ORC_BF16) return 0;
   if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16) return 0;
+  if (p->head_mode != ORC_HEADS_SEPARATE && p->head_mode != ORC_HEADS_JOINT) return 0;
   return 1;
 }
 
-/* ---- K_lr = K . A  (Sec. 4.2) -------------------------------------------- */
+/* ---- K_lr = K . A  (Sec. 3.2) -------------------------------------------- */
+
+/* joint-head design: row n of the flattened cache is (K[b,0,n,:], ..., K[b,H_kv-1,n,:]) */
+static int build_metadata_joint(const orc_params* p, const void* K, const float* A,
+                                void* K_lr, double* K_lr_exact) {
+  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
+  long b;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (b = 0; b < p->batch; ++b) {
+    for (int n = 0; n < N; ++n) {
+      const size_t orow = ((size_t)b * N + n) * r;
+      for (int j = 0; j < r; ++j) {
+        double acc = 0.0;
+        for (int k = 0; k < Hk; ++k) {
+          const size_t krow = (((size_t)b * Hk + k) * N + n) * d;
+          for (int i = 0; i < d; ++i) /* flattened column k*d + i */
+            acc += load_elem(K, p->kv_dtype, krow + i) * (double)A[((size_t)k * d + i) * r + j];
+        }
+        if (K_lr_exact) K_lr_exact[orow + j] = acc;
+        store_meta(K_lr, p->meta_dtype, orow + j, acc);
+      }
+    }
+  }
+  return 0;
+}
 
 int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
                           void* K_lr, double* K_lr_exact) {
   if (!params_ok(p) || !K || !A || !K_lr) return -1;
+  if (p->head_mode == ORC_HEADS_JOINT) return build_metadata_joint(p, K, A, K_lr, K_lr_exact);
   const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
   const long P = (long)p->batch * Hk;
   long pi;
@@ -86,7 +112,7 @@ int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
   return 0;
 }
 
-/* ---- prediction + selection (Sec. 4.3) ----------------------------------- */
+/* ---- prediction + selection (Sec. 3.3) ----------------------------------- */
 
 typedef struct {
   double score;
@@ -107,6 +133,84 @@ static int cmp_i32(const void* a, const void* b) {
   return (x > y) - (x < y);
 }
 
+/* "Scoring and selection": group representatives of the token scores s[0..N), the M
+ * best groups (ties to the lower index) in ascending index order.  g is scratch for
+ * NG entries; gs_out (NG doubles) and boundary (2 doubles) are nullable. */
+static void select_groups(const orc_params* p, const double* s, scored_group* g, int32_t* out,
+                          double* gs_out, double* boundary) {
+  const int G = p->group_size, M = p->n_select, NG = p->ctx_len / G;
+  for (int j = 0; j < NG; ++j) {
+    double rep;
+    if (p->reduce == ORC_REDUCE_MEAN) {
+      rep = 0.0;
+      for (int t = 0; t < G; ++t) rep += s[(size_t)j * G + t];
+      rep /= (double)G;
+    } else {
+      rep = s[(size_t)j * G];
+      for (int t = 1; t < G; ++t)
+        if (s[(size_t)j * G + t] > rep) rep = s[(size_t)j * G + t];
+    }
+    g[j].score = rep;
+    g[j].index = j;
+    if (gs_out) gs_out[j] = rep;
+  }
+  qsort(g, (size_t)NG, sizeof(scored_group), cmp_scored);
+  for (int m = 0; m < M; ++m) out[m] = g[m].index;
+  qsort(out, (size_t)M, sizeof(int32_t), cmp_i32);
+  if (boundary) {
+    boundary[0] = g[M - 1].score;
+    boundary[1] = (M < NG) ? g[M].score : -INFINITY;
+  }
+}
+
+/* joint-head design: every query head h scores the sequence's single K_lr with its
+ * low-rank query q[h] . A_{g(h)}, A_k being rows k*d .. k*d+d-1 of the adapter (Eq. 1) */
+static int predict_select_joint(const orc_params* p, const void* q, const void* K_lr,
+                                const float* A, int32_t* idx, double* gs_out, double* s_out,
+                                double* boundary) {
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim, r = p->rank;
+  const int N = p->ctx_len, M = p->n_select, NG = N / p->group_size, qpk = Hq / Hk;
+  int failed = 0;
+  long b;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (b = 0; b < p->batch; ++b) {
+    double* q_lr = (double*)malloc(sizeof(double) * (size_t)Hq * r);
+    double* s = (double*)malloc(sizeof(double) * (size_t)N);
+    scored_group* g = (scored_group*)malloc(sizeof(scored_group) * (size_t)NG);
+    if (!q_lr || !s || !g) {
+      failed = 1;
+      free(q_lr); free(s); free(g);
+      continue;
+    }
+    for (int h = 0; h < Hq; ++h) {
+      const float* Ak = A + (size_t)(h / qpk) * d * r; /* block of the shared KV head */
+      const size_t qrow = ((size_t)b * Hq + h) * d;
+      for (int j = 0; j < r; ++j) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i)
+          acc += load_elem(q, p->kv_dtype, qrow + i) * (double)Ak[(size_t)i * r + j];
+        q_lr[(size_t)h * r + j] = acc;
+      }
+    }
+    for (int n = 0; n < N; ++n) {
+      const size_t row = ((size_t)b * N + n) * r;
+      double tot = 0.0;
+      for (int h = 0; h < Hq; ++h) {
+        double acc = 0.0;
+        for (int j = 0; j < r; ++j)
+          acc += q_lr[(size_t)h * r + j] * load_elem(K_lr, p->meta_dtype, row + j);
+        tot += acc;
+      }
+      s[n] = tot;
+      if (s_out) s_out[(size_t)b * N + n] = tot;
+    }
+    select_groups(p, s, g, idx + (size_t)b * M, gs_out ? gs_out + (size_t)b * NG : NULL,
+                  boundary ? boundary + b * 2 : NULL);
+    free(q_lr); free(s); free(g);
+  }
+  return failed ? -2 : 0;
+}
+
 int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
                           const float* A, int32_t* idx, double* gs_out, double* s_out,
                           double* boundary) {
@@ -115,6 +219,8 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
   const int N = p->ctx_len, G = p->group_size, M = p->n_select;
   const int NG = N / G, qpk = Hq / Hk;
   if (M < 1 || M > NG) return -1;
+  if (p->head_mode == ORC_HEADS_JOINT)
+    return predict_select_joint(p, q, K_lr, A, idx, gs_out, s_out, boundary);
   const long P = (long)p->batch * Hk;
   int failed = 0;
   long pi;
@@ -154,31 +260,8 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
       s[n] = tot;
       if (s_out) s_out[(size_t)pi * N + n] = tot;
     }
-    /* group representative */
-    for (int j = 0; j < NG; ++j) {
-      double rep;
-      if (p->reduce == ORC_REDUCE_MEAN) {
-        rep = 0.0;
-        for (int t = 0; t < G; ++t) rep += s[(size_t)j * G + t];
-        rep /= (double)G;
-      } else {
-        rep = s[(size_t)j * G];
-        for (int t = 1; t < G; ++t)
-          if (s[(size_t)j * G + t] > rep) rep = s[(size_t)j * G + t];
-      }
-      g[j].score = rep;
-      g[j].index = j;
-      if (gs_out) gs_out[(size_t)pi * NG + j] = rep;
-    }
-    /* top-M groups, then ascending index order */
-    qsort(g, (size_t)NG, sizeof(scored_group), cmp_scored);
-    int32_t* out = idx + (size_t)pi * M;
-    for (int m = 0; m < M; ++m) out[m] = g[m].index;
-    qsort(out, (size_t)M, sizeof(int32_t), cmp_i32);
-    if (boundary) {
-      boundary[pi * 2 + 0] = g[M - 1].score;
-      boundary[pi * 2 + 1] = (M < NG) ? g[M].score : -INFINITY;
-    }
+    select_groups(p, s, g, idx + (size_t)pi * M, gs_out ? gs_out + (size_t)pi * NG : NULL,
+                  boundary ? boundary + pi * 2 : NULL);
     free(q_lr); free(s); free(g);
   }
   return failed ? -2 : 0;
@@ -228,7 +311,8 @@ int oracle_sparse_attn(const orc_params* p, const void* q, const void* K, const 
   const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
   const int G = p->group_size, M = p->n_select, NG = p->ctx_len / G;
   if (M < 1 || M > NG) return -1;
-  for (long i = 0; i < (long)p->batch * Hk * M; ++i)
+  const int joint = p->head_mode == ORC_HEADS_JOINT; /* one selection per sequence */
+  for (long i = 0; i < (long)p->batch * (joint ? 1 : Hk) * M; ++i)
     if (idx[i] < 0 || idx[i] >= NG) return -1;
   const double scale = resolve_scale(p);
   const long BH = (long)p->batch * Hq;
@@ -238,7 +322,7 @@ int oracle_sparse_attn(const orc_params* p, const void* q, const void* K, const 
   for (bh = 0; bh < BH; ++bh) {
     const int b = (int)(bh / Hq), h = (int)(bh % Hq);
     const int k = h / (Hq / Hk);
-    const int32_t* sel = idx + ((size_t)b * Hk + k) * M;
+    const int32_t* sel = idx + (joint ? (size_t)b : (size_t)b * Hk + k) * M;
     int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)M * G);
     if (!tokens) { failed = 1; continue; }
     for (int m = 0; m < M; ++m)

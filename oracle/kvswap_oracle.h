@@ -9,10 +9,18 @@
  * Conventions (all arrays contiguous, row-major, host memory):
  *   K, V    [B, H_kv, N, d]   storage dtype kv_dtype
  *   q       [B, H_q, d]       storage dtype kv_dtype
- *   A       [H_kv, d, r]      fp32 (per-KV-head adapter, Sec. 4.2 design (a))
+ *   A       [H_kv, d, r]      fp32 (per-KV-head adapter, Sec. 3.2 design (a))
  *   K_lr    [B, H_kv, N, r]   storage dtype meta_dtype
  *   idx     [B, H_kv, M]      int32 group indices, ascending
  *   g(h) = h / (H_q / H_kv)   query head -> shared KV head (Eq. 1)
+ * Joint-head mode (head_mode = ORC_HEADS_JOINT; Sec. 3.2 design (b), the one the
+ * paper adopts): the keys of all KV heads of a token are flattened into one row
+ * of H_kv*d values (head-major) and projected by a single adapter; there is one
+ * K_lr row per token and one selection per sequence:
+ *   A       [H_kv * d, r]     fp32; rows k*d .. k*d+d-1 form A_k of Eq. (1)
+ *   K_lr    [B, N, r]
+ *   idx     [B, M]            shared by all KV heads of the sequence
+ *   gs, s, boundary           [B, NG], [B, N], [B, 2]
  * Storage dtypes: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns).  Stored
  * values are widened to fp64 exactly; every sum is an fp64 sum in natural
  * index order.
@@ -21,7 +29,10 @@
  * A = I gives exact q.K scores; exactly rank-r keys give exact scores; both
  * sides of Eq. (1) agree; G = 1 is plain token top-k; selecting every group
  * equals dense softmax attention; planted ties resolve to the lower index;
- * closed-form softmax cases; bf16 rounding at known midpoints.
+ * closed-form softmax cases; bf16 rounding at known midpoints.  Joint mode: numpy
+ * brute force; one KV head makes both modes coincide; a block-diagonal adapter
+ * makes the joint scores the sum of the per-head ones; identity adapter gives the
+ * sum of the exact logits of all heads; shared idx equals replicated idx.
  * The paper prints no worked numeric example of this path, so numeric parity
  * with the authors' own implementation is unpinned (parity unpinned on that
  * point only; every function below has the pins listed above).
@@ -37,37 +48,43 @@ extern "C" {
 
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 enum { ORC_REDUCE_MAX = 0, ORC_REDUCE_MEAN = 1 };
+enum { ORC_HEADS_SEPARATE = 0, ORC_HEADS_JOINT = 1 };
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim, rank; /* B, H_q, H_kv, d, r */
   int32_t ctx_len, group_size, n_select;                /* N, G, M            */
   int32_t kv_dtype, meta_dtype;                         /* ORC_F32 / ORC_BF16 */
   int32_t reduce;                                       /* ORC_REDUCE_*       */
+  int32_t head_mode;                                    /* ORC_HEADS_*        */
   int32_t n_threads;   /* OpenMP threads over the (b, kv head) problems; <=1: serial */
   double softmax_scale; /* 0 => 1/sqrt(d) */
 } orc_params;
 
-/* K_lr = K . A per KV head (Sec. 4.2), fp64 accumulation, then one rounding to
- * meta_dtype (round-to-nearest-even).  K_lr_exact (nullable, [B,H_kv,N,r]
- * doubles) receives the unrounded products.  Returns 0, or -1 on bad params. */
+/* K_lr = K . A per KV head, or Flatten(K) . A in joint mode (Sec. 3.2), fp64
+ * accumulation, then one rounding to meta_dtype (round-to-nearest-even).
+ * K_lr_exact (nullable, doubles, shape of K_lr) receives the unrounded products.
+ * Returns 0, or -1 on bad params. */
 int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
                           void* K_lr, double* K_lr_exact);
 
-/* Prediction and selection (Sec. 4.3, Eq. 1 and "Scoring and selection"):
+/* Prediction and selection (Sec. 3.3, Eq. 1 and "Scoring and selection"):
  *   q_lr[h]  = q[h] . A[g(h)]                          (low-rank query vector)
  *   s[n]     = sum_{h: g(h)=k} q_lr[h] . K_lr[n]       (raw logits summed over heads)
  *   gs[j]    = max (or mean) of s over the G tokens of group j
  *   idx      = the M groups with the largest gs, ties to the lower index,
  *              written in ascending index order.
  * Optional outputs (nullable): gs [B,H_kv,NG], s [B,H_kv,N],
- * boundary [B,H_kv,2] = {M-th largest gs, (M+1)-th largest gs (or -inf if M = NG)}. */
+ * boundary [B,H_kv,2] = {M-th largest gs, (M+1)-th largest gs (or -inf if M = NG)}.
+ * Joint mode: the sum runs over all H_q heads, each with the A_{g(h)} block of the
+ * adapter, against the single K_lr of the sequence; outputs lose the H_kv axis. */
 int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
                           const float* A, int32_t* idx, double* gs, double* s,
                           double* boundary);
 
 /* Softmax attention of each query head over the tokens of the selected groups
  * of its KV head only: out[b,h,:] in fp64.  idx is [B,H_kv,n_sel] with
- * n_sel = p->n_select; order of idx is irrelevant, duplicates are not allowed. */
+ * n_sel = p->n_select ([B,n_sel] in joint mode: every head of the sequence attends
+ * the same groups); order of idx is irrelevant, duplicates are not allowed. */
 int oracle_sparse_attn(const orc_params* p, const void* q, const void* K,
                        const void* V, const int32_t* idx, double* out);
 

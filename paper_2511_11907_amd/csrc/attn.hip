@@ -1,4 +1,4 @@
-// Attention over the selected KV groups only (Sec. 4.4: the attention kernel consumes
+// Attention over the selected KV groups only (Sec. 3.4: the attention kernel consumes
 // the groups the predictor chose; here they are gathered straight from the full
 // K/V in HBM, which stands in for the paper's preload buffer).
 //

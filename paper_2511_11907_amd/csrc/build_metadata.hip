@@ -1,4 +1,4 @@
-// Compact key metadata (Sec. 4.2): K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32
+// Compact key metadata (Sec. 3.2): K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32
 // accumulation over the head dimension in natural order, one rounding to the
 // metadata dtype.  Runs at prefill and when new groups are appended, outside the
 // per-step latency.

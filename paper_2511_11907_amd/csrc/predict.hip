@@ -1,4 +1,4 @@
-// Prediction pass over the compact key metadata (Sec. 4.3, Eq. 1 and "Scoring and
+// Prediction pass over the compact key metadata (Sec. 3.3, Eq. 1 and "Scoring and
 // selection"): for every (sequence, KV head) problem, project the query heads
 // that share the KV head into the rank-r space, stream all N rows of K_lr once,
 // and write one representative score per group of G consecutive tokens.

@@ -1,4 +1,4 @@
-// Top-M selection kernel (Sec. 4.3, "TopK"): one workgroup of 1024 lanes per (sequence,
+// Top-M selection kernel (Sec. 3.3, "TopK"): one workgroup of 1024 lanes per (sequence,
 // KV head) problem runs kvs::topk_block on that problem's group scores, either from
 // scratch (kvs_select_topk) or starting from the histogram the prediction kernel left
 // in the workspace (kvs_predict_select).  The small fill kernel that prepares a

@@ -1,4 +1,4 @@
-// Workgroup-level top-M selection (Sec. 4.3, "TopK"): the indices of the M largest fp32
+// Workgroup-level top-M selection (Sec. 3.3, "TopK"): the indices of the M largest fp32
 // scores of one problem, ties to the lower index, written in ascending index order.
 //
 // Scores are compared as order-preserving 32-bit keys.  The key T of the M-th largest

@@ -59,3 +59,26 @@ def dense_attention(q, K, V, scale=None):
     B, Hk, N, _ = K.shape
     toks = [[np.arange(N) for _ in range(Hk)] for _ in range(B)]
     return attention_over_tokens(q, K, V, toks, scale)
+
+
+# ---- joint-head design: one adapter over the flattened keys, one selection per sequence ----
+def flatten_keys(K):
+    """[B,H_kv,N,d] -> [B,N,H_kv*d], head-major inside a row (Flatten(K) of Sec. 3.2)."""
+    B, Hk, N, d = K.shape
+    return np.transpose(K, (0, 2, 1, 3)).reshape(B, N, Hk * d)
+
+
+def joint_metadata(K, A):
+    """K_lr = Flatten(K) . A with A given as [H_kv,d,r] (= [(H_kv d), r] row-major)."""
+    Hk, d, r = A.shape
+    return flatten_keys(K) @ A.reshape(Hk * d, r)
+
+
+def joint_scores(q, K_lr, A):
+    """s[b,n] = sum over ALL query heads of (q_h . A_{g(h)}) . K_lr[b,n]  (Eq. 1)."""
+    B, Hq, d = q.shape
+    Hk = A.shape[0]
+    qpk = Hq // Hk
+    A_of_head = np.repeat(A, qpk, axis=0)                  # [Hq,d,r]: block of each head's KV head
+    q_lr = np.einsum("bhd,hdr->bhr", q, A_of_head)
+    return np.einsum("bhr,bnr->bn", q_lr, K_lr)

@@ -93,7 +93,7 @@ def test_mean_reduce_matches_brute_force():
 
 
 # --------------------------------------------------------------------------
-# metadata construction, Sec. 4.2: K_lr = K . A
+# metadata construction, Sec. 3.2: K_lr = K . A
 # --------------------------------------------------------------------------
 def test_build_metadata_with_selection_adapter_copies_columns():
     """A whose column j is the unit vector e_perm[j] makes K_lr[n, j] = K[n, perm[j]]
@@ -156,7 +156,7 @@ def test_bf16_rounding_matches_neighbour_search_and_torch():
 
 
 # --------------------------------------------------------------------------
-# prediction, Sec. 4.3 / Eq. (1)
+# prediction, Sec. 3.3 / Eq. (1)
 # --------------------------------------------------------------------------
 def test_identity_adapter_gives_exact_qk_scores():
     """r = d and A = I: K_lr = K and the token importance is sum_h q_h . K[n] exactly."""

@@ -4,7 +4,7 @@ Every tensor is drawn from a counter-based generator (numpy Philox) keyed by
 (seed, layer, sequence, kv head, tensor id), so any single (sequence, kv head)
 problem can be regenerated alone, on any machine, without generating the rest.
 
-The recipe mirrors the premise of the method (Sec. 4.2-4.3 of the paper): keys
+The recipe mirrors the premise of the method (Sec. 3.2-4.3 of the paper): keys
 of one KV head live close to a low-dimensional subspace (so a rank-r adapter
 captures them), and a small set of tokens dominates the scores.
 
@@ -14,7 +14,7 @@ captures them), and a small set of tokens dominates the scores.
     V[l,s,k]         : N(0,1)
     q[l,s,h]         : N(0,1)
     A[l,k]           : top-r right singular vectors of sequence 0's K[l,0,k]
-                       (the offline adapter of Sec. 4.2, fitted on a
+                       (the offline adapter of Sec. 3.2, fitted on a
                        "calibration" sequence and reused for the whole batch)
 
 Values are cast to the config's storage dtype (fp32, or bf16 with
@@ -179,7 +179,7 @@ def make_q(cfg: Config, layer: int, seq: int) -> np.ndarray:
 
 
 def fit_adapter(k_calib: np.ndarray, rank: int) -> np.ndarray:
-    """Offline low-rank adapter (Sec. 4.2): top-`rank` right singular vectors of
+    """Offline low-rank adapter (Sec. 3.2): top-`rank` right singular vectors of
     the calibration keys [N, d], as an fp32 [d, rank] matrix with orthonormal
     columns, ordered by decreasing singular value.  Computed from the
     eigen-decomposition of the d x d Gram matrix in fp64; each column's sign is
