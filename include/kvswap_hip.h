@@ -9,10 +9,19 @@
  *   attend  : out[h] = softmax(scale * q[h] . K[sel]^T) . V[sel]    over the selected
  *             groups' tokens only                                   (Sec. 3.4, KV cache manager)
  * with the compact metadata K_lr = K . A built once per token (Sec. 3.2).
- * The paper adopts one joint adapter for all KV heads; this library implements
- * its per-head design (a): one adapter A[k] (d x r), one K_lr and one selection
- * per KV head.  The full K/V cache lives in device memory (it stands in for the
- * paper's disk tier plus preload buffer).
+ * Sec. 3.2 considers two designs of the adapter and both are implemented
+ * (kvs_params.head_mode):
+ *   KVS_HEADS_SEPARATE  design (a): one adapter A[k] (d x r), one K_lr and one
+ *                       selection per KV head, as written above;
+ *   KVS_HEADS_JOINT     design (b), the one the paper adopts: the keys of all KV
+ *                       heads of a token are flattened into one row of H_kv*d values
+ *                       (head-major) and projected by a single adapter
+ *                       A [(H_kv*d) x r]; one K_lr row per token; the token score
+ *                       is summed over ALL query heads, head h using the block
+ *                       A_{g(h)} = rows g(h)*d .. g(h)*d+d-1 of the adapter (Eq. 1);
+ *                       one selection per sequence, shared by all its KV heads.
+ * The full K/V cache lives in device memory (it stands in for the paper's disk
+ * tier plus preload buffer).
  *
  * Memory: every pointer below is a DEVICE pointer unless it says "host".  All
  * tensors are contiguous and row-major, 16-byte aligned:
@@ -25,6 +34,9 @@
  *                                   ascending as written by kvs_predict_select
  *   group_scores  [B, H_kv, N/G]    fp32
  * g(h) = h / (H_q / H_kv).
+ * In joint mode the per-selection tensors have no H_kv axis: K_lr [B, N, r],
+ * idx [B, M], group_scores [B, N/G]; A has the same memory layout as above
+ * ([H_kv*d, r] row-major == [H_kv, d, r]).
  *
  * Ownership: the caller owns every buffer.  The library allocates nothing,
  * frees nothing, keeps no state between calls and never synchronises; all work
@@ -46,9 +58,10 @@
  * ABI.  Contents of idx are NOT validated on the device: out-of-range indices
  * passed to kvs_sparse_decode_attn are a caller error.
  *
- * Supported shapes: d in {64, 128}; r in {16, 32, 64, 128} with r <= d;
- * G in {1, 2, 4, 8, 16}; H_q / H_kv in {1, 2, 4, 8}; N % G == 0;
- * 1 <= M <= N/G; N/G <= 32768; B * H_kv <= 65535; N * d < 2^31.
+ * Supported shapes: d in {64, 128}; r in {16, 32, 64, 128} with r <= d
+ * (r <= H_kv*d in joint mode); G in {1, 2, 4, 8, 16}; H_q / H_kv in {1, 2, 4, 8};
+ * N % G == 0; 1 <= M <= N/G; N/G <= 32768; B * H_kv <= 65535; N * d < 2^31;
+ * joint mode: H_kv * d <= 4096.
  */
 #ifndef KVSWAP_HIP_H
 #define KVSWAP_HIP_H
@@ -64,7 +77,7 @@ typedef enum {
   KVS_OK = 0,
   KVS_ERR_NULL = 1,        /* a required pointer is NULL                      */
   KVS_ERR_SHAPE = 2,       /* inconsistent or non-positive sizes              */
-  KVS_ERR_DTYPE = 3,       /* unknown dtype / reduce code                     */
+  KVS_ERR_DTYPE = 3,       /* unknown dtype / reduce / head-mode code         */
   KVS_ERR_UNSUPPORTED = 4, /* consistent but outside the supported set        */
   KVS_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small         */
   KVS_ERR_DEVICE = 6,      /* a HIP launch reported an error                  */
@@ -73,6 +86,7 @@ typedef enum {
 
 typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
 typedef enum { KVS_REDUCE_MAX = 0, KVS_REDUCE_MEAN = 1 } kvs_reduce;
+typedef enum { KVS_HEADS_SEPARATE = 0, KVS_HEADS_JOINT = 1 } kvs_head_mode;
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim, rank; /* B, H_q, H_kv, d, r          */
@@ -81,6 +95,7 @@ typedef struct {
   int32_t meta_dtype;    /* kvs_dtype of K_lr                                          */
   int32_t reduce;        /* kvs_reduce; MAX is the paper's ReduceMax                   */
   float softmax_scale;   /* 0 => 1/sqrt(d)                                             */
+  int32_t head_mode;     /* kvs_head_mode; SEPARATE (0) = one adapter per KV head      */
 } kvs_params;
 
 /* Bytes of workspace that any of the calls below may need for these params
@@ -96,8 +111,8 @@ kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t works
  * calls would return for them. */
 kvs_status kvs_check_params(const kvs_params* p);
 
-/* Sec. 3.2: K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32 accumulation, one rounding
- * (nearest-even) to meta_dtype.  Run at prefill and whenever new groups are
+/* Sec. 3.2: K_lr[b,k,n,:] = K[b,k,n,:] . A[k] (joint mode: K_lr[b,n,:] =
+ * Flatten(K)[b,n,:] . A), fp32 accumulation, one rounding (nearest-even) to meta_dtype.  Run at prefill and whenever new groups are
  * appended; not part of the per-step latency.  n_select is ignored. */
 kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A,
                               void* K_lr, void* stream);
@@ -107,7 +122,9 @@ kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A
  * indices of the M best groups per (b, kv head): ties go to the lower index,
  * output ascending.  Two launches: the streaming kernel also histograms the
  * scores, the selection kernel starts from that histogram.  group_scores may be
- * NULL; if given it receives gs. */
+ * NULL; if given it receives gs.  Joint mode: one more small launch first, which
+ * projects the head-summed queries of each sequence into the rank-r space (kept
+ * in the workspace); scores are summed over all query heads and idx is [B, M]. */
 kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_lr,
                               const float* A, int32_t* idx, float* group_scores,
                               void* workspace, size_t workspace_bytes, void* stream);
@@ -115,7 +132,8 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
 /* The two launches of kvs_predict_select as separate calls (same kernels).
  * kvs_predict_scores writes group_scores [B,H_kv,N/G] (required here);
  * kvs_select_topk reads them and writes idx.  workspace may be NULL in both: the
- * selection then builds its own score histogram.  If kvs_predict_scores is given a
+ * selection then builds its own score histogram (joint mode: kvs_predict_scores
+ * needs the workspace, KVS_ERR_WORKSPACE without).  If kvs_predict_scores is given a
  * workspace it also leaves the per-problem score histograms there, and the NEXT call
  * on that workspace must be kvs_select_topk with the same workspace and params (it
  * consumes the histograms and zeroes them again). */
@@ -126,7 +144,8 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* Sec. 3.4 (attention consumes only the selected KV groups): softmax attention
- * of every query head over the G*M tokens named by idx of its KV head, gathered
+ * of every query head over the G*M tokens named by idx of its KV head (joint
+ * mode: by the idx of its sequence), gathered
  * from the full K/V, fp32 online softmax, result rounded to kv_dtype.  One
  * launch (split over the selected groups, merged by the last workgroup). */
 kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K,

@@ -67,9 +67,10 @@ static int build_metadata_joint(const orc_params* p, const void* K, const float*
                                 void* K_lr, double* K_lr_exact) {
   const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
   long b;
-#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  int n;
+#pragma omp parallel for collapse(2) schedule(static) num_threads(p->n_threads > 1 ? p->n_threads : 1)
   for (b = 0; b < p->batch; ++b) {
-    for (int n = 0; n < N; ++n) {
+    for (n = 0; n < N; ++n) {
       const size_t orow = ((size_t)b * N + n) * r;
       for (int j = 0; j < r; ++j) {
         double acc = 0.0;

@@ -15,6 +15,7 @@ from . import build as _build
 
 KVS_F32, KVS_BF16 = 0, 1
 KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
+KVS_HEADS_SEPARATE, KVS_HEADS_JOINT = 0, 1
 
 EXPORTS = (
     "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
@@ -36,7 +37,7 @@ class _CParams(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32), ("reduce", ctypes.c_int32),
-        ("softmax_scale", ctypes.c_float),
+        ("softmax_scale", ctypes.c_float), ("head_mode", ctypes.c_int32),
     ]
 
 
@@ -54,15 +55,21 @@ class Params:
     meta_dtype: int = KVS_BF16
     reduce: int = KVS_REDUCE_MAX
     softmax_scale: float = 0.0
+    head_mode: int = KVS_HEADS_SEPARATE
 
     def _c(self) -> _CParams:
         return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                         self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
-                        self.meta_dtype, self.reduce, self.softmax_scale)
+                        self.meta_dtype, self.reduce, self.softmax_scale, self.head_mode)
 
     @property
     def n_groups(self) -> int:
         return self.ctx_len // self.group_size
+
+    @property
+    def sets(self) -> tuple:
+        """Leading axes of K_lr, idx and group_scores: (B, H_kv), or (B,) in joint-head mode."""
+        return (self.batch,) if self.head_mode == KVS_HEADS_JOINT else (self.batch, self.n_kv_heads)
 
 
 _lib = None
@@ -198,7 +205,7 @@ def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:
         ctypes.byref(c),
         _dev(K, kd, (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim), "K"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
         _stream(stream))
     _check(st, "kvs_build_metadata")
 
@@ -209,13 +216,13 @@ def kvs_predict_select(p: Params, q, K_lr, A, idx, group_scores, workspace, stre
     c = p._c()
     ws, nws = _ws(workspace)
     gs = ctypes.c_void_p(0) if group_scores is None else _dev(
-        group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores")
+        group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores")
     st = load_library().kvs_predict_select(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
         gs, ws, nws, _stream(stream))
     _check(st, "kvs_predict_select")
 
@@ -228,9 +235,9 @@ def kvs_predict_scores(p: Params, q, K_lr, A, group_scores, workspace=None, stre
     st = load_library().kvs_predict_scores(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
+        _dev(group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores"),
         ws, nws, _stream(stream))
     _check(st, "kvs_predict_scores")
 
@@ -241,8 +248,8 @@ def kvs_select_topk(p: Params, group_scores, idx, workspace=None, stream=None) -
     ws, nws = _ws(workspace)
     st = load_library().kvs_select_topk(
         ctypes.byref(c),
-        _dev(group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores"),
-        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _dev(group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores"),
+        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
         ws, nws, _stream(stream))
     _check(st, "kvs_select_topk")
 
@@ -257,7 +264,7 @@ def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None)
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
         _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
-        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
         _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
         ws, nws, _stream(stream))
     _check(st, "kvs_sparse_decode_attn")
@@ -270,14 +277,14 @@ def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspa
     ws, nws = _ws(workspace)
     kv_shape = (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim)
     gs = ctypes.c_void_p(0) if group_scores is None else _dev(
-        group_scores, torch.float32, (p.batch, p.n_kv_heads, p.n_groups), "group_scores")
+        group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores")
     st = load_library().kvs_decode_step(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, (p.batch, p.n_kv_heads, p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
         _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
-        _dev(idx, torch.int32, (p.batch, p.n_kv_heads, p.n_select), "idx"),
+        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
         gs,
         _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
         ws, nws, _stream(stream))

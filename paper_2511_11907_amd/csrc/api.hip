@@ -36,6 +36,9 @@ inline int target(const char* env_name, int dflt) {
 Plan make_plan(const kvs_params& p) {
   Plan pl{};
   pl.problems = p.batch * p.n_kv_heads;
+  const bool joint = p.head_mode == KVS_HEADS_JOINT;
+  pl.sets = joint ? p.batch : pl.problems;
+  pl.kv_heads_per_set = joint ? p.n_kv_heads : 1;
   pl.n_groups = p.ctx_len / p.group_size;
   pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
 
@@ -46,7 +49,7 @@ Plan make_plan(const kvs_params& p) {
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;
   pl.predict_units = ceil_div(p.ctx_len, pl.meta_rows_per_unit);
   {
-    const int want = ceil_div(target("KVS_PREDICT_WGS", kPredictTargetWgs), pl.problems);
+    const int want = ceil_div(target("KVS_PREDICT_WGS", kPredictTargetWgs), pl.sets);
     const int most = ceil_div(pl.predict_units, kPredictUnitsPerWgStep);
     const int chunks = want < 1 ? 1 : (want > most ? most : want);
     pl.predict_units_per_wg = round_up(ceil_div(pl.predict_units, chunks), kPredictUnitsPerWgStep);
@@ -69,17 +72,19 @@ Plan make_plan(const kvs_params& p) {
 
   size_t off = 0;
   // zero-on-entry area: [0, P) attention arrival counters, then one histogram of
-  // kSelectHistBins counters per problem
+  // kSelectHistBins counters per selection set
   pl.off_sync = off;
   pl.off_hist = align256((size_t)pl.problems * sizeof(int));
-  pl.sync_bytes = pl.off_hist + align256((size_t)pl.problems * kSelectHistBins * sizeof(int));
+  pl.sync_bytes = pl.off_hist + align256((size_t)pl.sets * kSelectHistBins * sizeof(int));
   off += pl.sync_bytes;
   pl.off_gs = off;
-  off += align256((size_t)pl.problems * pl.n_groups * sizeof(float));
+  off += align256((size_t)pl.sets * pl.n_groups * sizeof(float));
   pl.off_part_ml = off;
   off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * 2 * sizeof(float));
   pl.off_part_o = off;
   off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * p.head_dim * sizeof(float));
+  pl.off_qlr = off;  // low-rank queries of the joint-head mode
+  off += align256((size_t)pl.sets * p.rank * sizeof(float));
   pl.total_bytes = off;
   return pl;
 }
@@ -93,11 +98,13 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
     return KVS_ERR_SHAPE;
   if ((p->kv_dtype != KVS_F32 && p->kv_dtype != KVS_BF16) ||
       (p->meta_dtype != KVS_F32 && p->meta_dtype != KVS_BF16) ||
-      (p->reduce != KVS_REDUCE_MAX && p->reduce != KVS_REDUCE_MEAN))
+      (p->reduce != KVS_REDUCE_MAX && p->reduce != KVS_REDUCE_MEAN) ||
+      (p->head_mode != KVS_HEADS_SEPARATE && p->head_mode != KVS_HEADS_JOINT))
     return KVS_ERR_DTYPE;
   if (p->n_q_heads % p->n_kv_heads) return KVS_ERR_SHAPE;
   if (p->ctx_len % p->group_size) return KVS_ERR_SHAPE;
-  if (p->rank > p->head_dim) return KVS_ERR_SHAPE;
+  const bool joint = p->head_mode == KVS_HEADS_JOINT;
+  if (p->rank > (joint ? p->n_kv_heads : 1) * p->head_dim) return KVS_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return KVS_ERR_SHAPE;
   const int ng = p->ctx_len / p->group_size;
   if (need_select && (p->n_select < 1 || p->n_select > ng)) return KVS_ERR_SHAPE;
@@ -111,6 +118,7 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
   // index arithmetic inside the kernels is 32-bit per problem and 64-bit across problems
   if ((long long)p->ctx_len * p->head_dim >= (1ll << 31)) return KVS_ERR_UNSUPPORTED;
   if ((long long)p->batch * p->n_kv_heads > 65535) return KVS_ERR_UNSUPPORTED;  // gridDim.y
+  if (joint && (long long)p->n_kv_heads * p->head_dim > kJointMaxFlatDim) return KVS_ERR_UNSUPPORTED;
   return KVS_OK;
 }
 
@@ -180,7 +188,8 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
   float* gs = group_scores ? group_scores : (float*)((char*)workspace + pl.off_gs);
   hipStream_t st = (hipStream_t)stream;
   int* hist = (int*)((char*)workspace + pl.off_hist);
-  if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, hist, st))) != KVS_OK) return s;
+  float* qlr = pl.kv_heads_per_set > 1 ? (float*)((char*)workspace + pl.off_qlr) : nullptr;
+  if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, hist, qlr, st))) != KVS_OK) return s;
   return dev(launch_topk(*p, pl, gs, idx, hist, st));
 }
 
@@ -194,11 +203,14 @@ kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_
     return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
   int* hist = nullptr;
+  float* qlr = nullptr;
+  if (!workspace && pl.kv_heads_per_set > 1) return KVS_ERR_WORKSPACE;  // holds the low-rank queries
   if (workspace) {
     if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
     hist = (int*)((char*)workspace + pl.off_hist);
+    if (pl.kv_heads_per_set > 1) qlr = (float*)((char*)workspace + pl.off_qlr);
   }
-  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, hist, (hipStream_t)stream));
+  return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, hist, qlr, (hipStream_t)stream));
 }
 
 kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32_t* idx,
@@ -248,7 +260,7 @@ const char* kvs_status_str(kvs_status s) {
     case KVS_OK: return "ok";
     case KVS_ERR_NULL: return "a required pointer is NULL";
     case KVS_ERR_SHAPE: return "inconsistent sizes";
-    case KVS_ERR_DTYPE: return "unknown dtype or reduce code";
+    case KVS_ERR_DTYPE: return "unknown dtype, reduce or head-mode code";
     case KVS_ERR_UNSUPPORTED: return "shape outside the supported set";
     case KVS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case KVS_ERR_DEVICE: return "HIP launch failed";

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
     float* part_ml, float* part_o, typename E::storage* __restrict__ out,
-    int* __restrict__ arrivals, int n_kv_heads, int N, int M, int log2G, int units,
+    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int N, int M, int log2G, int units,
     int units_per_split, int n_splits, float scale_log2e) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPT = D / EPL;       // lanes per token row
@@ -78,7 +78,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 
   const typename E::storage* Kp = K + (size_t)p * N * D;
   const typename E::storage* Vp = V + (size_t)p * N * D;
-  const int32_t* sel = idx + (size_t)p * M;
+  // the selection of this problem's set: its own, or the one its sequence shares
+  const int32_t* sel = idx + (size_t)(p / kv_heads_per_set) * M;
   const int u0 = split * units_per_split;
   const int u1 = min(units, u0 + units_per_split);
 
@@ -246,7 +247,7 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
   const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
   hipLaunchKernelGGL((attn_partial_kernel<E, D, QPK>), grid, block, 0, st, (const S*)q, (const S*)K,
-                     (const S*)V, idx, part_ml, part_o, (S*)out, arrivals, p.n_kv_heads, p.ctx_len,
+                     (const S*)V, idx, part_ml, part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, p.ctx_len,
                      p.n_select, log2G,
                      pl.attn_units, pl.attn_units_per_split, pl.attn_splits, scale * kLog2e);
   return hipGetLastError();

@@ -1,10 +1,13 @@
 // Compact key metadata (Sec. 3.2): K_lr[b,k,n,:] = K[b,k,n,:] . A[k], fp32
 // accumulation over the head dimension in natural order, one rounding to the
 // metadata dtype.  Runs at prefill and when new groups are appended, outside the
-// per-step latency.
+// per-step latency.  In joint-head mode the row that is projected is the token's
+// keys of all KV heads side by side, K_lr[b,n,:] = sum_k K[b,k,n,:] . A_k with A_k
+// the k-th block of d rows of the single adapter: the same tile loop, run over the
+// KV heads with the accumulators kept.
 //
 // A workgroup owns a tile of 64 consecutive token rows of one (sequence, KV head)
-// problem.  The K tile is brought in with coalesced 16-byte loads and parked in
+// problem (of one sequence in joint-head mode).  The K tile is brought in with coalesced 16-byte loads and parked in
 // LDS as fp32 (row stride d+1 words, so the 64 lanes of a wave, one row each, hit
 // 64 different banks); wave w produces the w-th quarter of the r output columns
 // for all 64 rows, so the adapter entries it needs are the same for every lane of
@@ -20,46 +23,50 @@ constexpr int kMetaRows = 64;
 template <typename EK, typename EM, int RC>  // RC = r / 4 output columns per lane
 __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     const typename EK::storage* __restrict__ K, const float* __restrict__ A,
-    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int N, int d) {
+    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int heads_per_set, int N, int d) {
   constexpr int R = RC * 4;
   extern __shared__ float s_k[];  // [kMetaRows][d + 1]
   const int tid = threadIdx.x;
-  const int p = blockIdx.y, k = p % n_kv_heads;
+  const int set = blockIdx.y;  // (b, k), or b alone when the heads are projected jointly
   const int row0 = blockIdx.x * kMetaRows;
   const int ld = d + 1;
-
-  // stage the tile: 16 bytes per lane, consecutive lanes along the row
   constexpr int EPL = EK::kPerLane;
   const int lanes_per_row = d / EPL;
-  const typename EK::storage* Kp = K + ((size_t)p * N + row0) * d;
-  for (int i = tid; i < kMetaRows * lanes_per_row; i += kMetaThreads) {
-    const int r_ = i / lanes_per_row, cc = i % lanes_per_row;
-    float f[EPL];
-    if (row0 + r_ < N) {
-      const uint4 v = *reinterpret_cast<const uint4*>(Kp + (size_t)r_ * d + (size_t)cc * EPL);
-      unpack16<EK>(v, f);
-    } else {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) f[e] = 0.f;
-    }
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) s_k[r_ * ld + cc * EPL + e] = f[e];
-  }
-  lds_barrier();
-
   const int row = tid & (kMetaRows - 1);
   const int jq = __builtin_amdgcn_readfirstlane(tid / kMetaRows);  // wave-uniform column quarter
-  const float* Ak = A + (size_t)k * d * R + (size_t)jq * RC;
   float acc[RC];
 #pragma unroll
   for (int j = 0; j < RC; ++j) acc[j] = 0.f;
-  for (int i = 0; i < d; ++i) {
-    const float kv = s_k[row * ld + i];
+
+  for (int kk = 0; kk < heads_per_set; ++kk) {
+    const int p = set * heads_per_set + kk;  // (b, k) problem whose keys are staged
+    const int k = p % n_kv_heads;
+    if (kk > 0) lds_barrier();               // everyone is done with the previous tile
+    // stage the tile: 16 bytes per lane, consecutive lanes along the row
+    const typename EK::storage* Kp = K + ((size_t)p * N + row0) * d;
+    for (int i = tid; i < kMetaRows * lanes_per_row; i += kMetaThreads) {
+      const int r_ = i / lanes_per_row, cc = i % lanes_per_row;
+      float f[EPL];
+      if (row0 + r_ < N) {
+        const uint4 v = *reinterpret_cast<const uint4*>(Kp + (size_t)r_ * d + (size_t)cc * EPL);
+        unpack16<EK>(v, f);
+      } else {
 #pragma unroll
-    for (int j = 0; j < RC; ++j) acc[j] = fmaf(kv, Ak[(size_t)i * R + j], acc[j]);
+        for (int e = 0; e < EPL; ++e) f[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_k[r_ * ld + cc * EPL + e] = f[e];
+    }
+    lds_barrier();
+    const float* Ak = A + (size_t)k * d * R + (size_t)jq * RC;
+    for (int i = 0; i < d; ++i) {
+      const float kv = s_k[row * ld + i];
+#pragma unroll
+      for (int j = 0; j < RC; ++j) acc[j] = fmaf(kv, Ak[(size_t)i * R + j], acc[j]);
+    }
   }
   if (row0 + row < N) {
-    typename EM::storage* o = K_lr + ((size_t)p * N + row0 + row) * R + (size_t)jq * RC;
+    typename EM::storage* o = K_lr + ((size_t)set * N + row0 + row) * R + (size_t)jq * RC;
 #pragma unroll
     for (int j = 0; j < RC; ++j) {
       if constexpr (EM::kBytes == 2) o[j] = float_to_bf16_bits(acc[j]);
@@ -73,11 +80,11 @@ namespace {
 template <typename EK, typename EM, int RC>
 hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* K, const float* A,
                       void* K_lr, hipStream_t st) {
-  dim3 grid((p.ctx_len + kMetaRows - 1) / kMetaRows, pl.problems), block(kMetaThreads);
+  dim3 grid((p.ctx_len + kMetaRows - 1) / kMetaRows, pl.sets), block(kMetaThreads);
   const size_t lds = (size_t)kMetaRows * (p.head_dim + 1) * sizeof(float);
   hipLaunchKernelGGL((build_metadata_kernel<EK, EM, RC>), grid, block, lds, st,
                      (const typename EK::storage*)K, A, (typename EM::storage*)K_lr, p.n_kv_heads,
-                     p.ctx_len, p.head_dim);
+                     pl.kv_heads_per_set, p.ctx_len, p.head_dim);
   return hipGetLastError();
 }
 

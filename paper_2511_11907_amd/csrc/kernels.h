@@ -16,13 +16,15 @@ constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per C
 constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs in flight
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
-constexpr int kAttnMaxSplitsPerProblem = 256;
-constexpr int kAttnMaxGroupsPerWg = 512;       // selected groups one workgroup stages in LDS  // the merge keeps one weight per split in LDS
+constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
+constexpr int kJointMaxFlatDim = 4096;          // H_kv * d the query projection kernel stages in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
 // call; kvs_workspace_bytes uses the same numbers).
 struct Plan {
-  int problems;          // P = B * H_kv
+  int problems;          // P = B * H_kv: attention problems
+  int sets;              // selection sets: P, or B in joint-head mode (one K_lr, one idx each)
+  int kv_heads_per_set;  // 1, or H_kv in joint-head mode
   int n_groups;          // NG = N / G
   int q_per_kv;          // H_q / H_kv
   // predict
@@ -39,7 +41,7 @@ struct Plan {
   int attn_splits;          // workgroups per problem
   // workspace layout (byte offsets, 256-byte aligned).  The arrival counters at
   // off_sync must be zero when a call starts; every call leaves them zero.
-  size_t off_sync, sync_bytes, off_hist, off_gs, off_part_ml, off_part_o, total_bytes;
+  size_t off_sync, sync_bytes, off_hist, off_gs, off_part_ml, off_part_o, off_qlr, total_bytes;
 };
 
 Plan make_plan(const kvs_params& p);
@@ -48,8 +50,10 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
                                  const float* A, void* K_lr, hipStream_t st);
 // hist == nullptr: scores only.  Otherwise the kernel also adds the histogram of the top
 // 12 key bits of every score to `hist` (kSelectHistBins ints per problem, zero on entry).
+// qlr: joint-head mode only (nullptr otherwise): pl.sets * r floats of scratch that receive
+// the low-rank queries from a small projection kernel launched first.
 hipError_t launch_predict(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                          const float* A, float* gs, int* hist, hipStream_t st);
+                          const float* A, float* gs, int* hist, float* qlr, hipStream_t st);
 // hist == nullptr: the selection builds its own histogram.  Otherwise it starts from the
 // finished per-problem histograms and leaves them zeroed.
 hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int32_t* idx,

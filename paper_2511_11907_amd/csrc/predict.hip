@@ -14,6 +14,15 @@
 // in-register all-reduce over those LPR lanes and the group max with a second
 // all-reduce over the lanes (or consecutive units) that hold the group's rows.
 //
+// Joint-head mode (Sec. 3.2 design (b)): there is one K_lr per sequence and the score is
+// summed over all query heads, head h projected with the block A_{g(h)} of the single
+// adapter.  The sum still commutes:
+//   q_lr = sum_k (sum_{h: g(h)=k} q[h]) . A_k = qcat . A,   qcat = the per-KV-head query
+//                                                            sums laid side by side
+// a contraction over H_kv*d values.  It is done once per sequence by a small kernel of
+// its own (project_query_kernel); the streaming kernel then starts from the r finished
+// values instead of projecting in its prologue.
+//
 // With HIST the kernel also prepares the selection: while a group score is still in a
 // register its top 12 key bits are counted in a workgroup-local LDS histogram, and at
 // the end the non-empty bins are added to the problem's histogram in global memory.
@@ -36,7 +45,8 @@ template <typename E, int R, int G, bool HIST>
 __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     const void* __restrict__ q, int q_is_bf16, const typename E::storage* __restrict__ K_lr,
     const float* __restrict__ A, float* gs, int n_kv_heads, int q_per_kv, int d,
-    int N, int units, int units_per_wg, int mean, int* __restrict__ hist) {
+    int N, int units, int units_per_wg, int mean, int* __restrict__ hist,
+    const float* __restrict__ qlr) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPR = R / EPL;          // lanes per row
   constexpr int RPU = kWave / LPR;      // rows per unit
@@ -91,17 +101,22 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   constexpr int kSpanMax = 128 / NSL;       // adapter rows per lane at d = 128
   const int pj = tid % R, psl = tid / R;
   const int span = d / NSL;
+  const bool project = (qlr == nullptr);  // uniform: false when the low-rank query is given
   float qsum_part = 0.f;
-  if (tid < d) {
-    for (int hh = 0; hh < q_per_kv; ++hh)
-      qsum_part += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + tid);
-  }
   float a_reg[kSpanMax];
-  {
+  float qr[EPL];
+  if (project) {
+    if (tid < d) {
+      for (int hh = 0; hh < q_per_kv; ++hh)
+        qsum_part += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + tid);
+    }
     const float* Ak = A + (size_t)k * d * R;
 #pragma unroll
     for (int i = 0; i < kSpanMax; ++i)
       a_reg[i] = Ak[(size_t)min(psl * span + i, d - 1) * R + pj];  // rows past the span are never used
+  } else {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qr[e] = qlr[(size_t)p * R + c * EPL + e];
   }
   int ub = u0;  // base of the current workgroup step
   if (ub < u1) issue(ub);
@@ -110,10 +125,10 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     for (int i = tid; i < kTopkBins; i += kPredictThreads) s_hist[i] = 0;
   }
 
-  // ---- low-rank query vector of this KV head (head-summed) --------------------
-  if (tid < d) s_qsum[tid] = qsum_part;
-  lds_barrier();
-  {
+  if (project) {
+    // ---- low-rank query vector of this KV head (head-summed) --------------------
+    if (tid < d) s_qsum[tid] = qsum_part;
+    lds_barrier();
     float acc = 0.f;
 #pragma unroll
     for (int i = 0; i < kSpanMax; ++i)
@@ -127,10 +142,12 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
       s_qlr[tid] = tot;
     }
     lds_barrier();
-  }
-  float qr[EPL];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) qr[e] = s_qlr[c * EPL + e];
+    for (int e = 0; e < EPL; ++e) qr[e] = s_qlr[c * EPL + e];
+  } else if constexpr (HIST) {
+    lds_barrier();  // the histogram is cleared before anyone counts into it
+  }
+
   const float inv_g = 1.0f / (float)G;
 
   while (ub < u1) {
@@ -197,46 +214,92 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   }
 }
 
+
+// Joint-head mode: q_lr[b,:] = qcat[b,:] . A for one sequence per workgroup, where
+// qcat[k*d + i] = sum_{h: g(h)=k} q[b,h,i] and A is [(H_kv*d), R].  Lane (slice, j)
+// sums every NSL-th row of column j (consecutive lanes read consecutive floats of a
+// row), the slices are added through LDS.
+constexpr int kProjectThreads = 1024;
+
+template <int R>
+__global__ __launch_bounds__(kProjectThreads) void project_query_kernel(
+    const void* __restrict__ q, int q_is_bf16, const float* __restrict__ A,
+    float* __restrict__ qlr, int n_kv_heads, int q_per_kv, int d) {
+  constexpr int NSL = kProjectThreads / R;
+  __shared__ float s_qcat[kJointMaxFlatDim];
+  __shared__ float s_part[kProjectThreads];
+  const int tid = threadIdx.x, b = blockIdx.x;
+  const int L = n_kv_heads * d;  // flattened length, <= kJointMaxFlatDim
+  const int n_q_heads = n_kv_heads * q_per_kv;
+  for (int i = tid; i < L; i += kProjectThreads) {
+    const int k = i / d, e = i % d;
+    float sum = 0.f;
+    for (int hh = 0; hh < q_per_kv; ++hh)
+      sum += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + e);
+    s_qcat[i] = sum;
+  }
+  lds_barrier();
+  const int j = tid % R, sl = tid / R;
+  float acc = 0.f;
+#pragma unroll 8
+  for (int i = sl; i < L; i += NSL) acc = fmaf(s_qcat[i], A[(size_t)i * R + j], acc);
+  s_part[tid] = acc;
+  lds_barrier();
+  if (tid < R) {
+    float tot = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < NSL; ++s) tot += s_part[s * R + tid];
+    qlr[(size_t)b * R + tid] = tot;
+  }
+}
+
 namespace {
 
 template <typename E, int R, int G>
 hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                      const float* A, float* gs, int* hist, hipStream_t st) {
-  dim3 grid(pl.predict_chunks, pl.problems), block(kPredictThreads);
+                      const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
+  dim3 grid(pl.predict_chunks, pl.sets), block(kPredictThreads);
   const int q_bf16 = (int)(p.kv_dtype == KVS_BF16), mean = (int)(p.reduce == KVS_REDUCE_MEAN);
+  if (qlr) {
+    hipLaunchKernelGGL((project_query_kernel<R>), dim3(pl.sets), dim3(kProjectThreads), 0, st, q,
+                       q_bf16, A, qlr, p.n_kv_heads, pl.q_per_kv, p.head_dim);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (hist)
     hipLaunchKernelGGL((predict_kernel<E, R, G, true>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
-                       p.head_dim, p.ctx_len, pl.predict_units, pl.predict_units_per_wg, mean, hist);
+                       p.head_dim, p.ctx_len, pl.predict_units, pl.predict_units_per_wg, mean, hist,
+                       (const float*)qlr);
   else
     hipLaunchKernelGGL((predict_kernel<E, R, G, false>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
                        p.head_dim, p.ctx_len, pl.predict_units, pl.predict_units_per_wg, mean,
-                       (int*)nullptr);
+                       (int*)nullptr, (const float*)qlr);
   return hipGetLastError();
 }
 
 template <typename E, int R>
 hipError_t launch_g(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                    const float* A, float* gs, int* hist, hipStream_t st) {
+                    const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
   switch (p.group_size) {
-    case 1: return launch_one<E, R, 1>(p, pl, q, K_lr, A, gs, hist, st);
-    case 2: return launch_one<E, R, 2>(p, pl, q, K_lr, A, gs, hist, st);
-    case 4: return launch_one<E, R, 4>(p, pl, q, K_lr, A, gs, hist, st);
-    case 8: return launch_one<E, R, 8>(p, pl, q, K_lr, A, gs, hist, st);
-    case 16: return launch_one<E, R, 16>(p, pl, q, K_lr, A, gs, hist, st);
+    case 1: return launch_one<E, R, 1>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 2: return launch_one<E, R, 2>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 4: return launch_one<E, R, 4>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 8: return launch_one<E, R, 8>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 16: return launch_one<E, R, 16>(p, pl, q, K_lr, A, gs, hist, qlr, st);
   }
   return hipErrorInvalidValue;
 }
 
 template <typename E>
 hipError_t launch_r(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                    const float* A, float* gs, int* hist, hipStream_t st) {
+                    const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
   switch (p.rank) {
-    case 16: return launch_g<E, 16>(p, pl, q, K_lr, A, gs, hist, st);
-    case 32: return launch_g<E, 32>(p, pl, q, K_lr, A, gs, hist, st);
-    case 64: return launch_g<E, 64>(p, pl, q, K_lr, A, gs, hist, st);
-    case 128: return launch_g<E, 128>(p, pl, q, K_lr, A, gs, hist, st);
+    case 16: return launch_g<E, 16>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 32: return launch_g<E, 32>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 64: return launch_g<E, 64>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 128: return launch_g<E, 128>(p, pl, q, K_lr, A, gs, hist, qlr, st);
   }
   return hipErrorInvalidValue;
 }
@@ -244,9 +307,9 @@ hipError_t launch_r(const kvs_params& p, const Plan& pl, const void* q, const vo
 }  // namespace
 
 hipError_t launch_predict(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
-                          const float* A, float* gs, int* hist, hipStream_t st) {
-  if (p.meta_dtype == KVS_BF16) return launch_r<BF16Elem>(p, pl, q, K_lr, A, gs, hist, st);
-  return launch_r<F32Elem>(p, pl, q, K_lr, A, gs, hist, st);
+                          const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
+  if (p.meta_dtype == KVS_BF16) return launch_r<BF16Elem>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+  return launch_r<F32Elem>(p, pl, q, K_lr, A, gs, hist, qlr, st);
 }
 
 }  // namespace kvs

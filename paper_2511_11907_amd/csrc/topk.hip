@@ -19,7 +19,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
 
 hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int32_t* idx,
                        int* hist, hipStream_t st) {
-  dim3 grid(pl.problems), block(kTopkThreads);
+  dim3 grid(pl.sets), block(kTopkThreads);
   hipLaunchKernelGGL(topk_kernel, grid, block, 0, st, gs, idx, pl.n_groups, p.n_select, hist);
   return hipGetLastError();
 }

@@ -38,7 +38,8 @@ def kv_params(cfg: Config, **over) -> kv.Params:
     d = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
              head_dim=cfg.head_dim, rank=cfg.rank, ctx_len=cfg.ctx_len,
              group_size=cfg.group_size, n_select=cfg.n_select,
-             kv_dtype=dt_code(cfg.dtype), meta_dtype=dt_code(cfg.dtype))
+             kv_dtype=dt_code(cfg.dtype), meta_dtype=dt_code(cfg.dtype),
+             head_mode=kv.KVS_HEADS_JOINT if cfg.joint else kv.KVS_HEADS_SEPARATE)
     d.update(over)
     return kv.Params(**d)
 
@@ -48,7 +49,8 @@ def orc_shape(cfg: Config, n_threads: int = 8, **over) -> oracle.Shape:
     d = dict(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
              head_dim=cfg.head_dim, rank=cfg.rank, ctx_len=cfg.ctx_len,
              group_size=cfg.group_size, n_select=cfg.n_select, kv_dtype=code, meta_dtype=code,
-             n_threads=n_threads)
+             n_threads=n_threads,
+             head_mode=oracle.HEADS_JOINT if cfg.joint else oracle.HEADS_SEPARATE)
     d.update(over)
     return oracle.Shape(**d)
 
@@ -119,19 +121,21 @@ def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bo
     # metadata: oracle-rounded K_lr is the reference and the input of the next step
     klr_ref, klr_exact = oracle.build_metadata(sh, L.K, L.A, want_exact=True)
     if check_meta:
-        klr_gpu = torch.empty((B, Hk, N, r), dtype=D.K.dtype, device=DEV)
+        klr_gpu = torch.empty(p.sets + (N, r), dtype=D.K.dtype, device=DEV)
         kv.kvs_build_metadata(p, D.K, D.A, klr_gpu)
         torch.cuda.synchronize()
-        absdot = np.einsum("bknd,kdr->bknr", np.abs(storage_to_f32(L.K)).astype(np.float64),
-                           np.abs(L.A).astype(np.float64))
+        # joint-head mode contracts over the H_kv*d flattened key row
+        absdot = np.einsum("bknd,kdr->bnr" if cfg.joint else "bknd,kdr->bknr",
+                           np.abs(storage_to_f32(L.K)).astype(np.float64), np.abs(L.A).astype(np.float64))
+        terms = cfg.head_dim * (Hk if cfg.joint else 1)
         stats["meta_mismatch"] = compare_metadata(to_host_storage(klr_gpu), klr_ref, klr_exact,
-                                                  absdot, cfg.head_dim, cfg.dtype)
+                                                  absdot, terms, cfg.dtype)
 
     ws = workspace(p)
     klr_dev = to_dev(klr_ref)
     ref = oracle.predict_select(sh, L.q, klr_ref, L.A)
-    idx = torch.full((B, Hk, M), -1, dtype=torch.int32, device=DEV)
-    gs = torch.full((B, Hk, cfg.n_groups), float("nan"), dtype=torch.float32, device=DEV)
+    idx = torch.full(p.sets + (M,), -1, dtype=torch.int32, device=DEV)
+    gs = torch.full(p.sets + (cfg.n_groups,), float("nan"), dtype=torch.float32, device=DEV)
     kv.kvs_predict_select(p, D.q, klr_dev, D.A, idx, gs, ws)
     torch.cuda.synchronize()
     gs_h, idx_h = gs.cpu().numpy().astype(np.float64), idx.cpu().numpy()
@@ -139,12 +143,12 @@ def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bo
     stats["gs_err"] = float(np.abs(gs_h - ref["gs"]).max() / scale)
     assert stats["gs_err"] <= GS_TOL, stats
     exact = 0
-    for b in range(B):
-        for k in range(Hk):
-            exact += check_index_margin(idx_h[b, k], ref["gs"][b, k], ref["boundary"][b, k],
-                                        f"{cfg.name} b={b} k={k}")
-            if (ref["boundary"][b, k][0] - ref["boundary"][b, k][1]) > MARGIN * scale:
-                np.testing.assert_array_equal(idx_h[b, k], ref["idx"][b, k])
+    flat = lambda a: a.reshape((-1,) + a.shape[len(p.sets):])   # one row per selection set
+    for i, (ig, gr, bd, ir) in enumerate(zip(flat(idx_h), flat(ref["gs"]), flat(ref["boundary"]),
+                                             flat(ref["idx"]))):
+        exact += check_index_margin(ig, gr, bd, f"{cfg.name} set {i}")
+        if (bd[0] - bd[1]) > MARGIN * scale:
+            np.testing.assert_array_equal(ig, ir)
     stats["idx_exact_problems"] = int(exact)
 
     # attention on the oracle's indices

@@ -67,6 +67,12 @@ def _p(**kw):
     (dict(n_q_heads=128), E_UNSUP),           # 16 heads per kv head
     (dict(group_size=1, ctx_len=65536, n_select=10), E_UNSUP),  # NG > 32768
     (dict(group_size=1, ctx_len=32768, n_select=10), OK),
+    # joint-head mode: one adapter over the H_kv*d flattened keys
+    (dict(head_mode=1), OK),
+    (dict(head_mode=1, rank=128, head_dim=64), OK),          # r may exceed d, not H_kv*d
+    (dict(head_mode=1, n_kv_heads=1, n_q_heads=4, rank=128, head_dim=64), E_SHAPE),
+    (dict(head_mode=1, n_kv_heads=64, n_q_heads=64), E_UNSUP),  # H_kv*d > 4096
+    (dict(head_mode=2), E_DTYPE),
 ])
 def test_check_params(kw, code):
     assert kv.kvs_check_params(_p(**kw)) == code
@@ -82,6 +88,16 @@ def test_workspace_covers_scores_and_partials():
     assert ws >= 8 * 8192 * 4 + 8 * 4 * 130 * 4 + 2 * 8 * 4  # scores, one split, counters
     assert ws % 256 == 0
     assert kv.kvs_workspace_bytes(_p(batch=8)) > ws
+
+
+def test_joint_mode_needs_less_workspace_for_scores_and_a_workspace_for_the_projection():
+    sep, jnt = _p(batch=8), _p(batch=8, head_mode=1)
+    assert kv.kvs_workspace_bytes(jnt) < kv.kvs_workspace_bytes(sep)   # one score row per sequence
+    lib = kv.load_library()
+    fake, null = ctypes.c_void_p(0x10000), ctypes.c_void_p(0)
+    c = jnt._c()
+    # the low-rank queries live in the workspace: scoring without one is refused on the host
+    assert lib.kvs_predict_scores(ctypes.byref(c), fake, fake, fake, fake, null, 0, null) == E_WS
 
 
 def test_entry_points_reject_bad_arguments_before_any_launch():

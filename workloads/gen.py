@@ -33,6 +33,7 @@ import numpy as np
 # tensor ids entering the generator key
 _T_BASIS, _T_Z, _T_NOISE, _T_HEAVY, _T_V, _T_Q = 1, 2, 3, 4, 5, 6
 _SEQ_SHARED = 0xFFFF  # "sequence" slot of tensors shared by the whole batch
+_HEAD_SHARED = 0xFFFF  # "head" slot of draws shared by all KV heads (joint-head workloads)
 
 
 @dataclass(frozen=True)
@@ -53,6 +54,7 @@ class Config:
     heavy: float          # >= 1: heavy-hitter tokens per (sequence, kv head); < 1: fraction of tokens
     heavy_scale: float = 4.0
     seed: int = 0
+    joint: bool = False   # joint-head design: one adapter over the flattened keys of all KV heads
 
     @property
     def n_groups(self) -> int:
@@ -99,6 +101,8 @@ PRESETS = {
     # 36-layer stack, b=16, 16K, r=32, G=4, 5 % of 4096 groups
     "c5": Config("c5", 36, 16, 32, 8, 128, 16384, 32, 4, 205, "bf16", 32, 0.1, 16),
 }
+# the same workloads under the joint-head design (compression ratio H_kv*d/r = 32, 32, 16, 32)
+PRESETS.update({k + "j": v.replace(name=k + "j", joint=True) for k, v in list(PRESETS.items())})
 
 
 # --------------------------------------------------------------------------
@@ -156,7 +160,11 @@ def _basis(cfg: Config, layer: int, kv_head: int) -> np.ndarray:
 def make_problem_kv(cfg: Config, layer: int, seq: int, kv_head: int):
     """K and V of one (layer, sequence, kv head): storage arrays of shape [N, d]."""
     n, d = cfg.ctx_len, cfg.head_dim
-    z = _rng(cfg, layer, seq, kv_head, _T_Z).standard_normal((n, cfg.planted_rank), dtype=np.float32)
+    # joint-head workloads: the latent factors (and the heavy-hitter tokens) of a token are
+    # shared by all KV heads, so the flattened row [K_0 | ... | K_{H-1}] has the planted rank
+    # and one adapter over it can capture what rho columns capture per head
+    zh = _HEAD_SHARED if cfg.joint else kv_head
+    z = _rng(cfg, layer, seq, zh, _T_Z).standard_normal((n, cfg.planted_rank), dtype=np.float32)
     k = z @ _basis(cfg, layer, kv_head)
     del z
     if cfg.noise_std:
@@ -166,7 +174,7 @@ def make_problem_kv(cfg: Config, layer: int, seq: int, kv_head: int):
         del noise
     nh = cfg.n_heavy()
     if nh:
-        rows = _rng(cfg, layer, seq, kv_head, _T_HEAVY).choice(n, size=min(nh, n), replace=False)
+        rows = _rng(cfg, layer, seq, zh, _T_HEAVY).choice(n, size=min(nh, n), replace=False)
         k[rows] *= np.float32(cfg.heavy_scale)
     v = _rng(cfg, layer, seq, kv_head, _T_V).standard_normal((n, d), dtype=np.float32)
     return _store(k, cfg.dtype), _store(v, cfg.dtype)
@@ -202,7 +210,7 @@ class LayerInputs:
     K: np.ndarray   # [B, H_kv, N, d] storage (float32 or uint16 bf16 bits)
     V: np.ndarray   # [B, H_kv, N, d]
     q: np.ndarray   # [B, H_q, d]
-    A: np.ndarray   # [H_kv, d, r] float32
+    A: np.ndarray   # [H_kv, d, r] float32 (joint-head: the [(H_kv d), r] adapter, same layout)
 
 
 def make_layer(cfg: Config, layer: int = 0, workers: int = 8,
@@ -230,6 +238,10 @@ def make_layer(cfg: Config, layer: int = 0, workers: int = 8,
     q = np.stack([make_q(cfg, layer, seq_offset + s) for s in range(b)])
     if adapter_from is not None:
         A = np.ascontiguousarray(adapter_from, dtype=np.float32)
+    elif cfg.joint:
+        k0 = [K[0, k] if seq_offset == 0 else make_problem_kv(cfg, layer, 0, k)[0] for k in range(hk)]
+        flat = np.concatenate([storage_to_f32(x) for x in k0], axis=1)      # [N, H_kv*d], head-major
+        A = fit_adapter(flat, cfg.rank).reshape(hk, d, cfg.rank)
     else:
         A = np.empty((hk, d, cfg.rank), dtype=np.float32)
         for k in range(hk):
