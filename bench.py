@@ -37,13 +37,14 @@ CACHE_BYTES = 256e6 + 32e6     # last-level cache + the eight L2s
 # --------------------------------------------------------------------------------------
 def algorithmic_bytes(cfg) -> dict:
     P = cfg.batch * cfg.n_kv_heads
+    S = cfg.batch if cfg.joint else P      # selection sets: one K_lr, one score row, one idx each
     eb = cfg.elem_bytes
     NG, M = cfg.n_groups, cfg.n_select
     q_bytes = cfg.batch * cfg.n_q_heads * cfg.head_dim * eb
     a_bytes = cfg.n_kv_heads * cfg.head_dim * cfg.rank * 4
-    predict = P * cfg.ctx_len * cfg.rank * eb + q_bytes + a_bytes + P * NG * 4
-    topk = P * NG * 4 + P * M * 4
-    attn = P * M * 4 + 2 * P * M * cfg.group_size * cfg.head_dim * eb + q_bytes + q_bytes
+    predict = S * cfg.ctx_len * cfg.rank * eb + q_bytes + a_bytes + S * NG * 4
+    topk = S * NG * 4 + S * M * 4
+    attn = S * M * 4 + 2 * P * M * cfg.group_size * cfg.head_dim * eb + q_bytes + q_bytes
     return {"predict": predict, "topk": topk, "attn": attn, "step": predict + topk + attn}
 
 
@@ -61,7 +62,8 @@ class Workload:
         code = kv.KVS_F32 if cfg.dtype == "f32" else kv.KVS_BF16
         tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
         self.p = kv.Params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank,
-                           cfg.ctx_len, cfg.group_size, cfg.n_select, code, code)
+                           cfg.ctx_len, cfg.group_size, cfg.n_select, code, code,
+                           head_mode=kv.KVS_HEADS_JOINT if cfg.joint else kv.KVS_HEADS_SEPARATE)
         self.ws = torch.empty(kv.kvs_workspace_bytes(self.p) // 4, dtype=torch.float32, device=dev)
         kv.kvs_workspace_init(self.p, self.ws)
         self.slots = []
@@ -87,10 +89,11 @@ class Workload:
                 L = make_layer(cfg, layer=0, workers=16, seq_offset=c * B, adapter_from=A0)
                 A0 = L.A
             s = {"K": up(L.K), "V": up(L.V), "q": up(L.q), "A": up(L.A)}
-            s["K_lr"] = torch.empty((B, Hk, N, cfg.rank), dtype=tdt, device=dev)
+            sets = self.p.sets
+            s["K_lr"] = torch.empty(sets + (N, cfg.rank), dtype=tdt, device=dev)
             kv.kvs_build_metadata(self.p, s["K"], s["A"], s["K_lr"])
-            s["idx"] = torch.empty((B, Hk, cfg.n_select), dtype=torch.int32, device=dev)
-            s["gs"] = torch.empty((B, Hk, cfg.n_groups), dtype=torch.float32, device=dev)
+            s["idx"] = torch.empty(sets + (cfg.n_select,), dtype=torch.int32, device=dev)
+            s["gs"] = torch.empty(sets + (cfg.n_groups,), dtype=torch.float32, device=dev)
             s["out"] = torch.empty((B, cfg.n_q_heads, cfg.head_dim), dtype=tdt, device=dev)
             # a workspace of its own, so that layer-steps in flight together do not share one
             s["ws"] = torch.empty_like(self.ws)
@@ -258,7 +261,8 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
     P = cfg.batch * cfg.n_kv_heads
     nb = max(1, min(cfg.batch, 8 // cfg.n_kv_heads if cfg.n_kv_heads <= 8 else 1))
     sh = oracle.Shape(nb, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank, cfg.ctx_len,
-                      cfg.group_size, cfg.n_select, code, code, n_threads=1)
+                      cfg.group_size, cfg.n_select, code, code, n_threads=1,
+                      head_mode=oracle.HEADS_JOINT if cfg.joint else oracle.HEADS_SEPARATE)
     K, V, q = (np.ascontiguousarray(x[:nb]) for x in (L.K, L.V, L.q))
     klr = oracle.build_metadata(oracle.Shape(**{**sh.__dict__, "n_threads": 8}), K, L.A)  # untimed set-up
     reps, spent = 0, 0.0
@@ -329,7 +333,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=24)
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--config", default="c2",
+                    choices=["c1", "c2", "c3", "c4", "c5", "c1j", "c2j", "c3j", "c4j", "c5j"],
+                    help="workload; a trailing j = the same workload under the joint-head design")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--copies", type=int, default=None, help="rotating input copies (default: 3x the caches)")
     ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
@@ -388,7 +394,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv d={cfg.head_dim} "
                                f"N={cfg.ctx_len} b={cfg.batch} r={cfg.rank} G={cfg.group_size} "
-                               f"M={cfg.n_select} layers={cfg.layers} {cfg.dtype}",
+                               f"M={cfg.n_select} layers={cfg.layers} {cfg.dtype}"
+                               + (" joint-head" if cfg.joint else ""),
                    "mode": args.mode, "input_copies": main_res["copies"]},
         "step_hbm_gbps": main_res["step_gbps"],
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
