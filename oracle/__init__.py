@@ -26,7 +26,8 @@ class _Params(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("rank", ctypes.c_int32),
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32),
-        ("reduce", ctypes.c_int32), ("head_mode", ctypes.c_int32), ("n_threads", ctypes.c_int32),
+        ("reduce", ctypes.c_int32), ("head_mode", ctypes.c_int32), ("ctx_capacity", ctypes.c_int32),
+        ("n_threads", ctypes.c_int32),
         ("softmax_scale", ctypes.c_double),
     ]
 
@@ -47,12 +48,18 @@ class Shape:
     n_threads: int = 1
     softmax_scale: float = 0.0
     head_mode: int = HEADS_SEPARATE
+    ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
 
     def _c(self) -> _Params:
         return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                        self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
-                       self.meta_dtype, self.reduce, self.head_mode, self.n_threads,
-                       self.softmax_scale)
+                       self.meta_dtype, self.reduce, self.head_mode, self.ctx_capacity,
+                       self.n_threads, self.softmax_scale)
+
+    @property
+    def rows(self) -> int:
+        """Rows held per problem by K, V and K_lr."""
+        return self.ctx_capacity or self.ctx_len
 
     @property
     def n_groups(self) -> int:
@@ -78,11 +85,14 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_build_metadata.argtypes = [pp, vp, vp, vp, vp]
         _lib.oracle_predict_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
         _lib.oracle_sparse_attn.argtypes = [pp, vp, vp, vp, vp, vp]
+        i32 = ctypes.c_int32
+        _lib.oracle_sparse_attn_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i32, vp]
+        _lib.oracle_build_metadata_rows.argtypes = [pp, vp, vp, vp, vp, i32, i32]
         _lib.oracle_dense_attn.argtypes = [pp, vp, vp, vp, vp]
         _lib.oracle_round_to_bf16.argtypes = [ctypes.c_double]
         _lib.oracle_round_to_bf16.restype = ctypes.c_uint16
-        for f in (_lib.oracle_build_metadata, _lib.oracle_predict_select,
-                  _lib.oracle_sparse_attn, _lib.oracle_dense_attn):
+        for f in (_lib.oracle_build_metadata, _lib.oracle_predict_select, _lib.oracle_sparse_attn,
+                  _lib.oracle_dense_attn, _lib.oracle_sparse_attn_rb, _lib.oracle_build_metadata_rows):
             f.restype = ctypes.c_int
     return _lib
 
@@ -112,21 +122,40 @@ def _check(rc, what):
 def build_metadata(sh: Shape, K, A, want_exact: bool = False):
     """K_lr = K . A, rounded once to meta_dtype.  Returns storage array
     [B,H_kv,N,r] ([B,N,r] in joint mode) (and the unrounded fp64 products if want_exact)."""
-    K = _arr(K, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.head_dim), "K")
+    K = _arr(K, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_kv_heads, sh.rows, sh.head_dim), "K")
     A = _arr(A, np.float32, (sh.n_kv_heads, sh.head_dim, sh.rank), "A")
-    out = np.empty(sh.sets + (sh.ctx_len, sh.rank), dtype=_np_dtype(sh.meta_dtype))
-    exact = np.empty(out.shape, dtype=np.float64) if want_exact else None
+    # rows beyond ctx_len (capacity) are not computed: they come back as zeros
+    out = np.zeros(sh.sets + (sh.rows, sh.rank), dtype=_np_dtype(sh.meta_dtype))
+    exact = np.zeros(out.shape, dtype=np.float64) if want_exact else None
     c = sh._c()
     _check(lib().oracle_build_metadata(ctypes.byref(c), _ptr(K), _ptr(A), _ptr(out), _ptr(exact)),
            "oracle_build_metadata")
     return (out, exact) if want_exact else out
 
 
+def build_metadata_rows(sh: Shape, K, A, K_lr, first_row: int, n_rows: int, exact=None):
+    """Metadata of token rows [first_row, first_row + n_rows) written into K_lr in place
+    (and the unrounded products into `exact`, if given)."""
+    K = _arr(K, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_kv_heads, sh.rows, sh.head_dim), "K")
+    A = _arr(A, np.float32, (sh.n_kv_heads, sh.head_dim, sh.rank), "A")
+    if not (isinstance(K_lr, np.ndarray) and K_lr.flags.c_contiguous and K_lr.flags.writeable
+            and K_lr.dtype == np.dtype(_np_dtype(sh.meta_dtype))
+            and K_lr.shape == sh.sets + (sh.rows, sh.rank)):
+        raise ValueError("K_lr: need a writable contiguous array of the metadata shape and dtype")
+    if exact is not None and not (exact.dtype == np.float64 and exact.shape == K_lr.shape
+                                  and exact.flags.c_contiguous):
+        raise ValueError("exact: need a contiguous float64 array of the metadata shape")
+    c = sh._c()
+    _check(lib().oracle_build_metadata_rows(ctypes.byref(c), _ptr(K), _ptr(A), _ptr(K_lr),
+                                            _ptr(exact), int(first_row), int(n_rows)),
+           "oracle_build_metadata_rows")
+
+
 def predict_select(sh: Shape, q, K_lr, A):
     """Returns dict(idx [B,H_kv,M] int32 ascending, gs [B,H_kv,NG] f64,
     s [B,H_kv,N] f64, boundary [B,H_kv,2] f64); no H_kv axis in joint mode."""
     q = _arr(q, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_q_heads, sh.head_dim), "q")
-    K_lr = _arr(K_lr, _np_dtype(sh.meta_dtype), sh.sets + (sh.ctx_len, sh.rank), "K_lr")
+    K_lr = _arr(K_lr, _np_dtype(sh.meta_dtype), sh.sets + (sh.rows, sh.rank), "K_lr")
     A = _arr(A, np.float32, (sh.n_kv_heads, sh.head_dim, sh.rank), "A")
     P = sh.sets
     idx = np.empty(P + (sh.n_select,), dtype=np.int32)
@@ -139,22 +168,31 @@ def predict_select(sh: Shape, q, K_lr, A):
     return {"idx": idx, "gs": gs, "s": s, "boundary": bnd}
 
 
-def sparse_attn(sh: Shape, q, K, V, idx):
+def sparse_attn(sh: Shape, q, K, V, idx, rb_K=None, rb_V=None, rb_len: int = 0):
+    """Attention over the selected groups (and, if given, the first rb_len tokens of the
+    rolling buffer rb_K / rb_V [B,H_kv,capacity,d])."""
     q = _arr(q, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_q_heads, sh.head_dim), "q")
-    shape_kv = (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.head_dim)
+    shape_kv = (sh.batch, sh.n_kv_heads, sh.rows, sh.head_dim)
     K = _arr(K, _np_dtype(sh.kv_dtype), shape_kv, "K")
     V = _arr(V, _np_dtype(sh.kv_dtype), shape_kv, "V")
     idx = _arr(idx, np.int32, sh.sets + (sh.n_select,), "idx")
     out = np.empty((sh.batch, sh.n_q_heads, sh.head_dim), dtype=np.float64)
     c = sh._c()
-    _check(lib().oracle_sparse_attn(ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(out)),
-           "oracle_sparse_attn")
+    cap = 0
+    if rb_K is not None:
+        cap = rb_K.shape[2]
+        shape_rb = (sh.batch, sh.n_kv_heads, cap, sh.head_dim)
+        rb_K = _arr(rb_K, _np_dtype(sh.kv_dtype), shape_rb, "rb_K")
+        rb_V = _arr(rb_V, _np_dtype(sh.kv_dtype), shape_rb, "rb_V")
+    _check(lib().oracle_sparse_attn_rb(ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                       _ptr(rb_K), _ptr(rb_V), int(rb_len), int(cap), _ptr(out)),
+           "oracle_sparse_attn_rb")
     return out
 
 
 def dense_attn(sh: Shape, q, K, V):
     q = _arr(q, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_q_heads, sh.head_dim), "q")
-    shape_kv = (sh.batch, sh.n_kv_heads, sh.ctx_len, sh.head_dim)
+    shape_kv = (sh.batch, sh.n_kv_heads, sh.rows, sh.head_dim)
     K = _arr(K, _np_dtype(sh.kv_dtype), shape_kv, "K")
     V = _arr(V, _np_dtype(sh.kv_dtype), shape_kv, "V")
     out = np.empty((sh.batch, sh.n_q_heads, sh.head_dim), dtype=np.float64)

@@ -57,25 +57,32 @@ static int params_ok(const orc_params* p) {
   if (p->kv_dtype != ORC_F32 && p->kv_dtype != ORC_BF16) return 0;
   if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16) return 0;
   if (p->head_mode != ORC_HEADS_SEPARATE && p->head_mode != ORC_HEADS_JOINT) return 0;
+  if (p->ctx_capacity != 0 && p->ctx_capacity < p->ctx_len) return 0;
   return 1;
+}
+
+/* rows allocated per problem in K, V and K_lr */
+static size_t row_capacity(const orc_params* p) {
+  return (size_t)(p->ctx_capacity > 0 ? p->ctx_capacity : p->ctx_len);
 }
 
 /* ---- K_lr = K . A  (Sec. 3.2) -------------------------------------------- */
 
 /* joint-head design: row n of the flattened cache is (K[b,0,n,:], ..., K[b,H_kv-1,n,:]) */
 static int build_metadata_joint(const orc_params* p, const void* K, const float* A,
-                                void* K_lr, double* K_lr_exact) {
-  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
+                                void* K_lr, double* K_lr_exact, int row0, int row1) {
+  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank;
+  const size_t cap = row_capacity(p);
   long b;
   int n;
 #pragma omp parallel for collapse(2) schedule(static) num_threads(p->n_threads > 1 ? p->n_threads : 1)
   for (b = 0; b < p->batch; ++b) {
-    for (n = 0; n < N; ++n) {
-      const size_t orow = ((size_t)b * N + n) * r;
+    for (n = row0; n < row1; ++n) {
+      const size_t orow = ((size_t)b * cap + n) * r;
       for (int j = 0; j < r; ++j) {
         double acc = 0.0;
         for (int k = 0; k < Hk; ++k) {
-          const size_t krow = (((size_t)b * Hk + k) * N + n) * d;
+          const size_t krow = (((size_t)b * Hk + k) * cap + n) * d;
           for (int i = 0; i < d; ++i) /* flattened column k*d + i */
             acc += load_elem(K, p->kv_dtype, krow + i) * (double)A[((size_t)k * d + i) * r + j];
         }
@@ -87,20 +94,25 @@ static int build_metadata_joint(const orc_params* p, const void* K, const float*
   return 0;
 }
 
-int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
-                          void* K_lr, double* K_lr_exact) {
+int oracle_build_metadata_rows(const orc_params* p, const void* K, const float* A,
+                               void* K_lr, double* K_lr_exact, int32_t first_row,
+                               int32_t n_rows) {
   if (!params_ok(p) || !K || !A || !K_lr) return -1;
-  if (p->head_mode == ORC_HEADS_JOINT) return build_metadata_joint(p, K, A, K_lr, K_lr_exact);
-  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank, N = p->ctx_len;
+  const size_t cap = row_capacity(p);
+  if (first_row < 0 || n_rows < 0 || (size_t)first_row + (size_t)n_rows > cap) return -1;
+  const int row0 = first_row, row1 = first_row + n_rows;
+  if (p->head_mode == ORC_HEADS_JOINT)
+    return build_metadata_joint(p, K, A, K_lr, K_lr_exact, row0, row1);
+  const int Hk = p->n_kv_heads, d = p->head_dim, r = p->rank;
   const long P = (long)p->batch * Hk;
   long pi;
 #pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
   for (pi = 0; pi < P; ++pi) {
     const int k = (int)(pi % Hk);
     const float* Ak = A + (size_t)k * d * r;
-    for (int n = 0; n < N; ++n) {
-      const size_t krow = ((size_t)pi * N + n) * d;
-      const size_t orow = ((size_t)pi * N + n) * r;
+    for (int n = row0; n < row1; ++n) {
+      const size_t krow = ((size_t)pi * cap + n) * d;
+      const size_t orow = ((size_t)pi * cap + n) * r;
       for (int j = 0; j < r; ++j) {
         double acc = 0.0;
         for (int i = 0; i < d; ++i)
@@ -111,6 +123,12 @@ int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
     }
   }
   return 0;
+}
+
+int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
+                          void* K_lr, double* K_lr_exact) {
+  if (!params_ok(p)) return -1;
+  return oracle_build_metadata_rows(p, K, A, K_lr, K_lr_exact, 0, p->ctx_len);
 }
 
 /* ---- prediction + selection (Sec. 3.3) ----------------------------------- */
@@ -194,7 +212,7 @@ static int predict_select_joint(const orc_params* p, const void* q, const void* 
       }
     }
     for (int n = 0; n < N; ++n) {
-      const size_t row = ((size_t)b * N + n) * r;
+      const size_t row = ((size_t)b * row_capacity(p) + n) * r;
       double tot = 0.0;
       for (int h = 0; h < Hq; ++h) {
         double acc = 0.0;
@@ -250,7 +268,7 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
     }
     /* token importance: per-head low-rank logits, summed over the heads */
     for (int n = 0; n < N; ++n) {
-      const size_t row = ((size_t)pi * N + n) * r;
+      const size_t row = ((size_t)pi * row_capacity(p) + n) * r;
       double tot = 0.0;
       for (int hh = 0; hh < qpk; ++hh) {
         double acc = 0.0;
@@ -270,32 +288,40 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
 
 /* ---- attention ----------------------------------------------------------- */
 
-/* softmax(scale * q.K[tok]) . V[tok] over the listed tokens of one (b, h) */
+/* One softmax over the listed cache tokens of one (b, h) followed by the first rb_len
+ * rolling-buffer tokens of its KV head: out = sum_t w_t V_t / sum_t w_t with
+ * w_t = exp(scale * q.K_t - max).  rb_K / rb_V may be NULL when rb_len is 0. */
 static int attend_tokens(const orc_params* p, const void* q, const void* K, const void* V,
-                         int b, int h, const int32_t* tokens, long n_tok, double scale,
+                         int b, int h, const int32_t* tokens, long n_tok, const void* rb_K,
+                         const void* rb_V, long rb_len, long rb_capacity, double scale,
                          double* out) {
-  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim, N = p->ctx_len;
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
   const int k = h / (Hq / Hk);
   const size_t qrow = ((size_t)b * Hq + h) * d;
-  const size_t kvbase = ((size_t)b * Hk + k) * (size_t)N * d;
-  double* z = (double*)malloc(sizeof(double) * (size_t)n_tok);
+  const size_t kvbase = ((size_t)b * Hk + k) * row_capacity(p) * d;
+  const size_t rbbase = ((size_t)b * Hk + k) * (size_t)rb_capacity * d;
+  const long total = n_tok + rb_len;
+  double* z = (double*)malloc(sizeof(double) * (size_t)total);
   if (!z) return -2;
   double zmax = -INFINITY;
-  for (long t = 0; t < n_tok; ++t) {
-    const size_t row = kvbase + (size_t)tokens[t] * d;
+  for (long t = 0; t < total; ++t) {
+    /* token t: a cache row, or (after all of those) a buffer row */
+    const void* src = t < n_tok ? K : rb_K;
+    const size_t row = t < n_tok ? kvbase + (size_t)tokens[t] * d : rbbase + (size_t)(t - n_tok) * d;
     double acc = 0.0;
     for (int i = 0; i < d; ++i)
-      acc += load_elem(q, p->kv_dtype, qrow + i) * load_elem(K, p->kv_dtype, row + i);
+      acc += load_elem(q, p->kv_dtype, qrow + i) * load_elem(src, p->kv_dtype, row + i);
     z[t] = scale * acc;
     if (z[t] > zmax) zmax = z[t];
   }
   double denom = 0.0;
   for (int i = 0; i < d; ++i) out[i] = 0.0;
-  for (long t = 0; t < n_tok; ++t) {
+  for (long t = 0; t < total; ++t) {
     const double w = exp(z[t] - zmax);
-    const size_t row = kvbase + (size_t)tokens[t] * d;
+    const void* src = t < n_tok ? V : rb_V;
+    const size_t row = t < n_tok ? kvbase + (size_t)tokens[t] * d : rbbase + (size_t)(t - n_tok) * d;
     denom += w;
-    for (int i = 0; i < d; ++i) out[i] += w * load_elem(V, p->kv_dtype, row + i);
+    for (int i = 0; i < d; ++i) out[i] += w * load_elem(src, p->kv_dtype, row + i);
   }
   for (int i = 0; i < d; ++i) out[i] /= denom;
   free(z);
@@ -308,7 +334,14 @@ static double resolve_scale(const orc_params* p) {
 
 int oracle_sparse_attn(const orc_params* p, const void* q, const void* K, const void* V,
                        const int32_t* idx, double* out) {
+  return oracle_sparse_attn_rb(p, q, K, V, idx, NULL, NULL, 0, 0, out);
+}
+
+int oracle_sparse_attn_rb(const orc_params* p, const void* q, const void* K, const void* V,
+                          const int32_t* idx, const void* rb_K, const void* rb_V,
+                          int32_t rb_len, int32_t rb_capacity, double* out) {
   if (!params_ok(p) || !q || !K || !V || !idx || !out) return -1;
+  if (rb_len < 0 || rb_len > rb_capacity || (rb_len > 0 && (!rb_K || !rb_V))) return -1;
   const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
   const int G = p->group_size, M = p->n_select, NG = p->ctx_len / G;
   if (M < 1 || M > NG) return -1;
@@ -328,7 +361,8 @@ int oracle_sparse_attn(const orc_params* p, const void* q, const void* K, const 
     if (!tokens) { failed = 1; continue; }
     for (int m = 0; m < M; ++m)
       for (int t = 0; t < G; ++t) tokens[(size_t)m * G + t] = sel[m] * G + t;
-    if (attend_tokens(p, q, K, V, b, h, tokens, (long)M * G, scale, out + (size_t)bh * d))
+    if (attend_tokens(p, q, K, V, b, h, tokens, (long)M * G, rb_K, rb_V, rb_len, rb_capacity,
+                      scale, out + (size_t)bh * d))
       failed = 1;
     free(tokens);
   }
@@ -349,7 +383,8 @@ int oracle_dense_attn(const orc_params* p, const void* q, const void* K, const v
     int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
     if (!tokens) { failed = 1; continue; }
     for (int n = 0; n < N; ++n) tokens[n] = n;
-    if (attend_tokens(p, q, K, V, b, h, tokens, N, scale, out + (size_t)bh * d)) failed = 1;
+    if (attend_tokens(p, q, K, V, b, h, tokens, N, NULL, NULL, 0, 0, scale, out + (size_t)bh * d))
+      failed = 1;
     free(tokens);
   }
   return failed ? -2 : 0;

@@ -21,6 +21,12 @@
  *   K_lr    [B, N, r]
  *   idx     [B, M]            shared by all KV heads of the sequence
  *   gs, s, boundary           [B, NG], [B, N], [B, 2]
+ * Capacity: if ctx_capacity > 0 the arrays K, V and K_lr hold ctx_capacity rows per
+ * (b, kv head) [per b for the joint K_lr] of which the first ctx_len are the cache
+ * (room for the groups a decode loop appends); 0 means exactly ctx_len rows.
+ * Rolling buffer (Sec. 3.4.1 "New KV entries management"): the newest tokens, not yet
+ * a complete group, live outside the cache in rb_K, rb_V [B, H_kv, rb_capacity, d]
+ * (first rb_len rows valid); they are never scored and always attended.
  * Storage dtypes: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns).  Stored
  * values are widened to fp64 exactly; every sum is an fp64 sum in natural
  * index order.
@@ -33,6 +39,11 @@
  * brute force; one KV head makes both modes coincide; a block-diagonal adapter
  * makes the joint scores the sum of the per-head ones; identity adapter gives the
  * sum of the exact logits of all heads; shared idx equals replicated idx.
+ * Rolling buffer / capacity: numpy brute force over the concatenated token list; an
+ * empty buffer changes nothing; a cache group moved into the buffer gives the same
+ * output; all groups + buffer equals dense attention over the concatenated cache;
+ * padded (capacity > ctx_len) arrays with poisoned padding give the compact results;
+ * metadata of a row range equals the same rows of the full build.
  * The paper prints no worked numeric example of this path, so numeric parity
  * with the authors' own implementation is unpinned (parity unpinned on that
  * point only; every function below has the pins listed above).
@@ -56,6 +67,7 @@ typedef struct {
   int32_t kv_dtype, meta_dtype;                         /* ORC_F32 / ORC_BF16 */
   int32_t reduce;                                       /* ORC_REDUCE_*       */
   int32_t head_mode;                                    /* ORC_HEADS_*        */
+  int32_t ctx_capacity; /* rows allocated per problem in K, V, K_lr; 0 => ctx_len      */
   int32_t n_threads;   /* OpenMP threads over the (b, kv head) problems; <=1: serial */
   double softmax_scale; /* 0 => 1/sqrt(d) */
 } orc_params;
@@ -66,6 +78,13 @@ typedef struct {
  * Returns 0, or -1 on bad params. */
 int oracle_build_metadata(const orc_params* p, const void* K, const float* A,
                           void* K_lr, double* K_lr_exact);
+
+/* The same for token rows first_row .. first_row + n_rows - 1 only (the metadata of
+ * newly completed groups, Sec. 3.4.1); other rows of K_lr / K_lr_exact are untouched.
+ * Rows may lie beyond ctx_len but must lie inside the capacity. */
+int oracle_build_metadata_rows(const orc_params* p, const void* K, const float* A,
+                               void* K_lr, double* K_lr_exact, int32_t first_row,
+                               int32_t n_rows);
 
 /* Prediction and selection (Sec. 3.3, Eq. 1 and "Scoring and selection"):
  *   q_lr[h]  = q[h] . A[g(h)]                          (low-rank query vector)
@@ -87,6 +106,14 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
  * the same groups); order of idx is irrelevant, duplicates are not allowed. */
 int oracle_sparse_attn(const orc_params* p, const void* q, const void* K,
                        const void* V, const int32_t* idx, double* out);
+
+/* The same with a rolling buffer: every head also attends the first rb_len tokens of
+ * its KV head's rows of rb_K / rb_V [B, H_kv, rb_capacity, d] (one softmax over the
+ * selected tokens and the buffer together).  rb_len = 0 is oracle_sparse_attn. */
+int oracle_sparse_attn_rb(const orc_params* p, const void* q, const void* K,
+                          const void* V, const int32_t* idx, const void* rb_K,
+                          const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                          double* out);
 
 /* Ordinary softmax attention over all N tokens. */
 int oracle_dense_attn(const orc_params* p, const void* q, const void* K,
