@@ -34,6 +34,11 @@
  *                                   ascending as written by kvs_predict_select
  *   group_scores  [B, H_kv, N/G]    fp32
  * g(h) = h / (H_q / H_kv).
+ * With ctx_capacity = C > 0 the N axis of K, V and K_lr has C >= N rows allocated
+ * (K, V [B, H_kv, C, d], K_lr [B, H_kv, C, r]); only the first N are the cache.
+ * Rolling buffer (Sec. 3.4.1): the newest tokens, which do not yet form a group,
+ * live in rb_K, rb_V [B, H_kv, rb_capacity, d] (kv_dtype), first rb_len rows valid;
+ * they are never scored and always attended (the *_rb calls).
  * In joint mode the per-selection tensors have no H_kv axis: K_lr [B, N, r],
  * idx [B, M], group_scores [B, N/G]; A has the same memory layout as above
  * ([H_kv*d, r] row-major == [H_kv, d, r]).
@@ -61,7 +66,7 @@
  * Supported shapes: d in {64, 128}; r in {16, 32, 64, 128} with r <= d
  * (r <= H_kv*d in joint mode); G in {1, 2, 4, 8, 16}; H_q / H_kv in {1, 2, 4, 8};
  * N % G == 0; 1 <= M <= N/G; N/G <= 32768; B * H_kv <= 65535; N * d < 2^31;
- * joint mode: H_kv * d <= 4096.
+ * joint mode: H_kv * d <= 4096; ctx_capacity * d < 2^31; rb_len <= 256.
  */
 #ifndef KVSWAP_HIP_H
 #define KVSWAP_HIP_H
@@ -96,6 +101,9 @@ typedef struct {
   int32_t reduce;        /* kvs_reduce; MAX is the paper's ReduceMax                   */
   float softmax_scale;   /* 0 => 1/sqrt(d)                                             */
   int32_t head_mode;     /* kvs_head_mode; SEPARATE (0) = one adapter per KV head      */
+  int32_t ctx_capacity;  /* rows allocated per (b, kv head) in K and V, and per selection
+                            set in K_lr; 0 => ctx_len.  Rows ctx_len .. capacity-1 are room
+                            for the groups a decode loop appends and are never read.       */
 } kvs_params;
 
 /* Bytes of workspace that any of the calls below may need for these params
@@ -116,6 +124,22 @@ kvs_status kvs_check_params(const kvs_params* p);
  * appended; not part of the per-step latency.  n_select is ignored. */
 kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A,
                               void* K_lr, void* stream);
+
+/* The same for token rows first_row .. first_row + n_rows - 1 only (they may lie
+ * beyond ctx_len, inside the capacity): the incremental update of the compressed K
+ * cache when new groups are completed (Sec. 3.4.1).  KVS_ERR_SHAPE if the range
+ * leaves the allocated rows. */
+kvs_status kvs_build_metadata_rows(const kvs_params* p, const void* K, const float* A,
+                                   void* K_lr, int32_t first_row, int32_t n_rows, void* stream);
+
+/* Sec. 3.4.1: a completed group leaves the rolling buffer.  Copies the first G rows
+ * of every (b, kv head) of rb_K / rb_V into cache rows ctx_len .. ctx_len+G-1 of K / V
+ * (written here) and builds the K_lr rows of the new group; two small launches.
+ * Needs ctx_len + G <= ctx_capacity and rb_capacity >= G (KVS_ERR_SHAPE otherwise).
+ * Afterwards the caller uses ctx_len + G and restarts (or shifts) its buffer. */
+kvs_status kvs_append_group(const kvs_params* p, const void* rb_K, const void* rb_V,
+                            int32_t rb_capacity, void* K, void* V, const float* A, void* K_lr,
+                            void* stream);
 
 /* Sec. 3.3 (Eq. 1, "Scoring and selection"): low-rank token scores summed over
  * the query heads of each KV head, group representative (max or mean), and the
@@ -152,6 +176,16 @@ kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void
                                   const void* V, const int32_t* idx, void* out,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same with a rolling buffer: every head also attends the first rb_len tokens of
+ * its KV head's rows of rb_K / rb_V, in one softmax with the selected tokens.
+ * rb_len = 0 (pointers may then be NULL) is kvs_sparse_decode_attn.  The buffer's
+ * tokens are handled by the last split of each problem; rb_len <= 256. */
+kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const void* K,
+                                     const void* V, const int32_t* idx, const void* rb_K,
+                                     const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                                     void* out, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
 /* One whole decode step of a layer: kvs_predict_select followed by
  * kvs_sparse_decode_attn on the same stream (three launches in all).  idx
  * receives the selection (it is an output here); group_scores may be NULL. */
@@ -159,6 +193,14 @@ kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
                            const float* A, const void* K, const void* V, int32_t* idx,
                            float* group_scores, void* out, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/* kvs_decode_step with the rolling buffer in the attention (kvs_predict_select, then
+ * kvs_sparse_decode_attn_rb). */
+kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_lr,
+                              const float* A, const void* K, const void* V, const void* rb_K,
+                              const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                              int32_t* idx, float* group_scores, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream);
 
 /* Static, NUL-terminated description of a status code (host pointer). */
 const char* kvs_status_str(kvs_status s);

@@ -8,5 +8,7 @@ from .binding import (  # noqa: F401
     KVS_F32, KVS_BF16, KVS_REDUCE_MAX, KVS_REDUCE_MEAN, KVS_HEADS_SEPARATE, KVS_HEADS_JOINT,
     KvsError, Params, load_library, library_path,
     kvs_check_params, kvs_workspace_bytes, kvs_workspace_init, kvs_status_str, kvs_version, kvs_last_device_error,
-    kvs_build_metadata, kvs_predict_select, kvs_predict_scores, kvs_select_topk, kvs_sparse_decode_attn, kvs_decode_step,
+    kvs_build_metadata, kvs_build_metadata_rows, kvs_append_group,
+    kvs_predict_select, kvs_predict_scores, kvs_select_topk,
+    kvs_sparse_decode_attn, kvs_sparse_decode_attn_rb, kvs_decode_step, kvs_decode_step_rb,
 )

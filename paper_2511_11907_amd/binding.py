@@ -18,9 +18,11 @@ KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
 KVS_HEADS_SEPARATE, KVS_HEADS_JOINT = 0, 1
 
 EXPORTS = (
-    "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata", "kvs_predict_select",
+    "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata",
+    "kvs_build_metadata_rows", "kvs_append_group", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
-    "kvs_sparse_decode_attn", "kvs_decode_step", "kvs_status_str", "kvs_version", "kvs_last_device_error",
+    "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_decode_step", "kvs_decode_step_rb",
+    "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
 
@@ -38,6 +40,7 @@ class _CParams(ctypes.Structure):
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32), ("reduce", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float), ("head_mode", ctypes.c_int32),
+        ("ctx_capacity", ctypes.c_int32),
     ]
 
 
@@ -56,11 +59,18 @@ class Params:
     reduce: int = KVS_REDUCE_MAX
     softmax_scale: float = 0.0
     head_mode: int = KVS_HEADS_SEPARATE
+    ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
 
     def _c(self) -> _CParams:
         return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                         self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
-                        self.meta_dtype, self.reduce, self.softmax_scale, self.head_mode)
+                        self.meta_dtype, self.reduce, self.softmax_scale, self.head_mode,
+                        self.ctx_capacity)
+
+    @property
+    def rows(self) -> int:
+        """Rows held per problem by K, V and K_lr."""
+        return self.ctx_capacity or self.ctx_len
 
     @property
     def n_groups(self) -> int:
@@ -103,6 +113,15 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_check_params.restype = ctypes.c_int
     lib.kvs_build_metadata.argtypes = [pp, vp, vp, vp, vp]
     lib.kvs_build_metadata.restype = ctypes.c_int
+    i32 = ctypes.c_int32
+    lib.kvs_build_metadata_rows.argtypes = [pp, vp, vp, vp, i32, i32, vp]
+    lib.kvs_build_metadata_rows.restype = ctypes.c_int
+    lib.kvs_append_group.argtypes = [pp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.kvs_append_group.restype = ctypes.c_int
+    lib.kvs_sparse_decode_attn_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.kvs_sparse_decode_attn_rb.restype = ctypes.c_int
+    lib.kvs_decode_step_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvs_decode_step_rb.restype = ctypes.c_int
     lib.kvs_predict_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_predict_select.restype = ctypes.c_int
     lib.kvs_predict_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
@@ -198,16 +217,50 @@ def kvs_workspace_init(p: Params, workspace, stream=None) -> None:
 
 
 def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:
+    kvs_build_metadata_rows(p, K, A, K_lr, 0, p.ctx_len, stream, _what="kvs_build_metadata")
+
+
+def kvs_build_metadata_rows(p: Params, K, A, K_lr, first_row: int, n_rows: int, stream=None,
+                            _what="kvs_build_metadata_rows") -> None:
     torch = _torch()
     kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
     c = p._c()
-    st = load_library().kvs_build_metadata(
+    st = load_library().kvs_build_metadata_rows(
         ctypes.byref(c),
-        _dev(K, kd, (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim), "K"),
+        _dev(K, kd, (p.batch, p.n_kv_heads, p.rows, p.head_dim), "K"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
+        int(first_row), int(n_rows), _stream(stream))
+    _check(st, _what)
+
+
+def _rb(p: Params, rb_K, rb_V, rb_len: int):
+    """Rolling-buffer tensors [B,H_kv,capacity,d] -> (K pointer, V pointer, len, capacity)."""
+    if rb_K is None or rb_V is None:
+        if rb_len:
+            raise ValueError("rb_len > 0 needs rb_K and rb_V")
+        return ctypes.c_void_p(0), ctypes.c_void_p(0), 0, 0
+    kd = _dtype_of(p.kv_dtype)
+    if rb_K.dim() != 4:
+        raise ValueError("rb_K must be [B, H_kv, capacity, d]")
+    cap = int(rb_K.shape[2])
+    shape = (p.batch, p.n_kv_heads, cap, p.head_dim)
+    return _dev(rb_K, kd, shape, "rb_K"), _dev(rb_V, kd, shape, "rb_V"), int(rb_len), cap
+
+
+def kvs_append_group(p: Params, rb_K, rb_V, K, V, A, K_lr, stream=None) -> None:
+    torch = _torch()
+    kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    c = p._c()
+    rk, rv, _, cap = _rb(p, rb_K, rb_V, 0)
+    kv_shape = (p.batch, p.n_kv_heads, p.rows, p.head_dim)
+    st = load_library().kvs_append_group(
+        ctypes.byref(c), rk, rv, cap,
+        _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
+        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+        _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
         _stream(stream))
-    _check(st, "kvs_build_metadata")
+    _check(st, "kvs_append_group")
 
 
 def kvs_predict_select(p: Params, q, K_lr, A, idx, group_scores, workspace, stream=None) -> None:
@@ -220,7 +273,7 @@ def kvs_predict_select(p: Params, q, K_lr, A, idx, group_scores, workspace, stre
     st = load_library().kvs_predict_select(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
         _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
         gs, ws, nws, _stream(stream))
@@ -235,7 +288,7 @@ def kvs_predict_scores(p: Params, q, K_lr, A, group_scores, workspace=None, stre
     st = load_library().kvs_predict_scores(
         ctypes.byref(c),
         _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
+        _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
         _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
         _dev(group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores"),
         ws, nws, _stream(stream))
@@ -255,37 +308,54 @@ def kvs_select_topk(p: Params, group_scores, idx, workspace=None, stream=None) -
 
 
 def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None) -> None:
+    kvs_sparse_decode_attn_rb(p, q, K, V, idx, None, None, 0, out, workspace, stream,
+                              _entry="kvs_sparse_decode_attn")
+
+
+def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, workspace, stream=None,
+                              _entry="kvs_sparse_decode_attn_rb") -> None:
     torch = _torch()
     kd = _dtype_of(p.kv_dtype)
     c = p._c()
     ws, nws = _ws(workspace)
-    kv_shape = (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim)
-    st = load_library().kvs_sparse_decode_attn(
-        ctypes.byref(c),
-        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
-        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
-        _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
-        ws, nws, _stream(stream))
-    _check(st, "kvs_sparse_decode_attn")
+    kv_shape = (p.batch, p.n_kv_heads, p.rows, p.head_dim)
+    args = [ctypes.byref(c),
+            _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+            _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
+            _dev(idx, torch.int32, p.sets + (p.n_select,), "idx")]
+    tail = [_dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"), ws, nws, _stream(stream)]
+    lib = load_library()
+    if _entry == "kvs_sparse_decode_attn":
+        st = lib.kvs_sparse_decode_attn(*args, *tail)
+    else:
+        st = lib.kvs_sparse_decode_attn_rb(*args, *_rb(p, rb_K, rb_V, rb_len), *tail)
+    _check(st, _entry)
 
 
 def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:
+    kvs_decode_step_rb(p, q, K_lr, A, K, V, None, None, 0, idx, group_scores, out, workspace, stream,
+                       _entry="kvs_decode_step")
+
+
+def kvs_decode_step_rb(p: Params, q, K_lr, A, K, V, rb_K, rb_V, rb_len, idx, group_scores, out,
+                       workspace, stream=None, _entry="kvs_decode_step_rb") -> None:
     torch = _torch()
     kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
     c = p._c()
     ws, nws = _ws(workspace)
-    kv_shape = (p.batch, p.n_kv_heads, p.ctx_len, p.head_dim)
+    kv_shape = (p.batch, p.n_kv_heads, p.rows, p.head_dim)
     gs = ctypes.c_void_p(0) if group_scores is None else _dev(
         group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores")
-    st = load_library().kvs_decode_step(
-        ctypes.byref(c),
-        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
-        _dev(K_lr, md, p.sets + (p.ctx_len, p.rank), "K_lr"),
-        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
-        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
-        gs,
-        _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"),
-        ws, nws, _stream(stream))
-    _check(st, "kvs_decode_step")
+    head = [ctypes.byref(c),
+            _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+            _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
+            _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+            _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V")]
+    tail = [_dev(idx, torch.int32, p.sets + (p.n_select,), "idx"), gs,
+            _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"), ws, nws, _stream(stream)]
+    lib = load_library()
+    if _entry == "kvs_decode_step":
+        st = lib.kvs_decode_step(*head, *tail)
+    else:
+        st = lib.kvs_decode_step_rb(*head, *_rb(p, rb_K, rb_V, rb_len), *tail)
+    _check(st, _entry)

@@ -39,6 +39,7 @@ Plan make_plan(const kvs_params& p) {
   const bool joint = p.head_mode == KVS_HEADS_JOINT;
   pl.sets = joint ? p.batch : pl.problems;
   pl.kv_heads_per_set = joint ? p.n_kv_heads : 1;
+  pl.ctx_rows = p.ctx_capacity > 0 ? p.ctx_capacity : p.ctx_len;
   pl.n_groups = p.ctx_len / p.group_size;
   pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
 
@@ -103,6 +104,7 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
     return KVS_ERR_DTYPE;
   if (p->n_q_heads % p->n_kv_heads) return KVS_ERR_SHAPE;
   if (p->ctx_len % p->group_size) return KVS_ERR_SHAPE;
+  if (p->ctx_capacity != 0 && p->ctx_capacity < p->ctx_len) return KVS_ERR_SHAPE;
   const bool joint = p->head_mode == KVS_HEADS_JOINT;
   if (p->rank > (joint ? p->n_kv_heads : 1) * p->head_dim) return KVS_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return KVS_ERR_SHAPE;
@@ -116,13 +118,26 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
   if (!is_pow2(qpk) || qpk > 8) return KVS_ERR_UNSUPPORTED;
   if (ng > 32768) return KVS_ERR_UNSUPPORTED;
   // index arithmetic inside the kernels is 32-bit per problem and 64-bit across problems
-  if ((long long)p->ctx_len * p->head_dim >= (1ll << 31)) return KVS_ERR_UNSUPPORTED;
+  const long long rows = p->ctx_capacity > 0 ? p->ctx_capacity : p->ctx_len;
+  if (rows * p->head_dim >= (1ll << 31)) return KVS_ERR_UNSUPPORTED;
   if ((long long)p->batch * p->n_kv_heads > 65535) return KVS_ERR_UNSUPPORTED;  // gridDim.y
   if (joint && (long long)p->n_kv_heads * p->head_dim > kJointMaxFlatDim) return KVS_ERR_UNSUPPORTED;
   return KVS_OK;
 }
 
 inline bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15u) != 0; }
+
+// rolling-buffer arguments of the *_rb calls -> RollingBuffer (len 0: no buffer at all)
+kvs_status check_rb(const void* rb_K, const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                    RollingBuffer* rb) {
+  if (rb_len < 0 || rb_capacity < 0 || rb_len > rb_capacity) return KVS_ERR_SHAPE;
+  if (rb_len > kRollingBufferMaxLen) return KVS_ERR_UNSUPPORTED;
+  if (rb_len == 0) return KVS_OK;
+  if (!rb_K || !rb_V) return KVS_ERR_NULL;
+  if (misaligned(rb_K) || misaligned(rb_V)) return KVS_ERR_ALIGN;
+  rb->K = rb_K, rb->V = rb_V, rb->len = rb_len, rb->capacity = rb_capacity;
+  return KVS_OK;
+}
 
 kvs_status check_workspace(const Plan& pl, const void* ws, size_t bytes) {
   if (!ws || misaligned(ws) || bytes < pl.total_bytes) return KVS_ERR_WORKSPACE;
@@ -162,8 +177,8 @@ kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t works
   return dev(launch_fill_zero((char*)workspace + pl.off_sync, pl.sync_bytes, (hipStream_t)stream));
 }
 
-kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A, void* K_lr,
-                              void* stream) {
+kvs_status kvs_build_metadata_rows(const kvs_params* p, const void* K, const float* A, void* K_lr,
+                                   int32_t first_row, int32_t n_rows, void* stream) {
   if (!p || !K || !A || !K_lr) return KVS_ERR_NULL;
   kvs_params q = *p;
   q.n_select = 1;  // not used by this call
@@ -171,7 +186,35 @@ kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A
   if (s != KVS_OK) return s;
   if (misaligned(K) || misaligned(A) || misaligned(K_lr)) return KVS_ERR_ALIGN;
   const Plan pl = make_plan(q);
-  return dev(launch_build_metadata(q, pl, K, A, K_lr, (hipStream_t)stream));
+  if (first_row < 0 || n_rows < 0 || (long long)first_row + n_rows > pl.ctx_rows) return KVS_ERR_SHAPE;
+  return dev(launch_build_metadata(q, pl, K, A, K_lr, first_row, n_rows, (hipStream_t)stream));
+}
+
+kvs_status kvs_build_metadata(const kvs_params* p, const void* K, const float* A, void* K_lr,
+                              void* stream) {
+  if (!p) return KVS_ERR_NULL;
+  return kvs_build_metadata_rows(p, K, A, K_lr, 0, p->ctx_len, stream);
+}
+
+kvs_status kvs_append_group(const kvs_params* p, const void* rb_K, const void* rb_V,
+                            int32_t rb_capacity, void* K, void* V, const float* A, void* K_lr,
+                            void* stream) {
+  if (!p || !rb_K || !rb_V || !K || !V || !A || !K_lr) return KVS_ERR_NULL;
+  kvs_params q = *p;
+  q.n_select = 1;  // not used by this call
+  kvs_status s = check_params(&q, false);
+  if (s != KVS_OK) return s;
+  if (misaligned(rb_K) || misaligned(rb_V) || misaligned(K) || misaligned(V) || misaligned(A) ||
+      misaligned(K_lr))
+    return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(q);
+  if (rb_capacity < q.group_size) return KVS_ERR_SHAPE;               // no complete group to move
+  if ((long long)q.ctx_len + q.group_size > pl.ctx_rows) return KVS_ERR_SHAPE;  // cache is full
+  RollingBuffer rb;
+  rb.K = rb_K, rb.V = rb_V, rb.len = q.group_size, rb.capacity = rb_capacity;
+  hipStream_t st = (hipStream_t)stream;
+  if ((s = dev(launch_append_rows(q, pl, rb, K, V, st))) != KVS_OK) return s;
+  return dev(launch_build_metadata(q, pl, K, A, K_lr, q.ctx_len, q.group_size, st));
 }
 
 kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_lr, const float* A,
@@ -228,12 +271,16 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
   return dev(launch_topk(*p, pl, group_scores, idx, hist, (hipStream_t)stream));
 }
 
-kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,
-                                  const int32_t* idx, void* out, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const void* K,
+                                     const void* V, const int32_t* idx, const void* rb_K,
+                                     const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                                     void* out, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
   if (!p || !q || !K || !V || !idx || !out) return KVS_ERR_NULL;
   kvs_status s = check_params(p, true);
   if (s != KVS_OK) return s;
+  RollingBuffer rb;
+  if ((s = check_rb(rb_K, rb_V, rb_len, rb_capacity, &rb)) != KVS_OK) return s;
   if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(out))
     return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
@@ -241,18 +288,38 @@ kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void
   float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
   float* part_o = (float*)((char*)workspace + pl.off_part_o);
   int* arrivals = (int*)((char*)workspace + pl.off_sync);
-  return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals,
+  return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb,
                          (hipStream_t)stream));
+}
+
+kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, void* out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  return kvs_sparse_decode_attn_rb(p, q, K, V, idx, nullptr, nullptr, 0, 0, out, workspace,
+                                   workspace_bytes, stream);
+}
+
+kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_lr, const float* A,
+                              const void* K, const void* V, const void* rb_K, const void* rb_V,
+                              int32_t rb_len, int32_t rb_capacity, int32_t* idx,
+                              float* group_scores, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!p || !q || !K_lr || !A || !K || !V || !idx || !out) return KVS_ERR_NULL;
+  RollingBuffer rb;  // validated before anything is launched
+  kvs_status s = check_rb(rb_K, rb_V, rb_len, rb_capacity, &rb);
+  if (s != KVS_OK) return s;
+  if (misaligned(K) || misaligned(V) || misaligned(out)) return KVS_ERR_ALIGN;
+  s = kvs_predict_select(p, q, K_lr, A, idx, group_scores, workspace, workspace_bytes, stream);
+  if (s != KVS_OK) return s;
+  return kvs_sparse_decode_attn_rb(p, q, K, V, idx, rb_K, rb_V, rb_len, rb_capacity, out,
+                                   workspace, workspace_bytes, stream);
 }
 
 kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr, const float* A,
                            const void* K, const void* V, int32_t* idx, float* group_scores,
                            void* out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!p || !q || !K_lr || !A || !K || !V || !idx || !out) return KVS_ERR_NULL;
-  kvs_status s = kvs_predict_select(p, q, K_lr, A, idx, group_scores, workspace, workspace_bytes,
-                                    stream);
-  if (s != KVS_OK) return s;
-  return kvs_sparse_decode_attn(p, q, K, V, idx, out, workspace, workspace_bytes, stream);
+  return kvs_decode_step_rb(p, q, K_lr, A, K, V, nullptr, nullptr, 0, 0, idx, group_scores, out,
+                            workspace, workspace_bytes, stream);
 }
 
 const char* kvs_status_str(kvs_status s) {

@@ -29,13 +29,17 @@ constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <typename E, int D, int QPK>
+// RB: the attended-token list continues into a rolling buffer (compiled out otherwise, so
+// the plain path pays nothing for it).
+template <typename E, int D, int QPK, bool RB>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
     float* part_ml, float* part_o, typename E::storage* __restrict__ out,
-    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int N, int M, int log2G, int units,
-    int units_per_split, int n_splits, float scale_log2e) {
+    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int ctx_rows, int M, int log2G,
+    int units, int units_per_split, int n_splits, float scale_log2e,
+    const typename E::storage* __restrict__ rb_K, const typename E::storage* __restrict__ rb_V,
+    int rb_len, int rb_capacity) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPT = D / EPL;       // lanes per token row
   constexpr int TPU = kWave / LPT;   // tokens per unit
@@ -76,29 +80,39 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     for (int e = 0; e < EPL; ++e) o[h][e] = 0.f;
   }
 
-  const typename E::storage* Kp = K + (size_t)p * N * D;
-  const typename E::storage* Vp = V + (size_t)p * N * D;
+  const typename E::storage* Kp = K + (size_t)p * ctx_rows * D;
+  const typename E::storage* Vp = V + (size_t)p * ctx_rows * D;
+  // rolling buffer (Sec. 3.4.1): the newest rb_len tokens follow the selected ones in the
+  // token list; they are read from their own small arrays
+  const typename E::storage* Kr = rb_K + (size_t)p * rb_capacity * D;
+  const typename E::storage* Vr = rb_V + (size_t)p * rb_capacity * D;
+  const int n_all = RB ? n_tok + rb_len : n_tok;
   // the selection of this problem's set: its own, or the one its sequence shares
   const int32_t* sel = idx + (size_t)(p / kv_heads_per_set) * M;
   const int u0 = split * units_per_split;
-  const int u1 = min(units, u0 + units_per_split);
+  // the splits partition the units of the selected tokens; the few units of the rolling
+  // buffer are taken by the last split
+  const int u1 = (split == n_splits - 1) ? units : min(units, u0 + units_per_split);
 
   for (int ub = u0 + wave * kAttnUnroll; ub < u1; ub += kAttnWaves * kAttnUnroll) {
-    bool ok[kAttnUnroll];
+    bool ok[kAttnUnroll], in_rb[kAttnUnroll];
     size_t off[kAttnUnroll];
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) {
-      const int tok = (ub + u) * TPU + ts;  // position in the selected-token list
-      ok[u] = (ub + u < u1) && (tok < n_tok);
-      const int grp = ok[u] ? sel[tok >> log2G] : 0;
-      const int row = (grp << log2G) + (tok & (G - 1));
+      const int tok = (ub + u) * TPU + ts;  // position in the attended-token list
+      ok[u] = (ub + u < u1) && (tok < n_all);
+      in_rb[u] = RB && ok[u] && (tok >= n_tok);
+      const int grp = (ok[u] && !in_rb[u]) ? sel[tok >> log2G] : 0;
+      const int row = in_rb[u] ? tok - n_tok : (grp << log2G) + (tok & (G - 1));
       off[u] = (size_t)(ok[u] ? row : 0) * D + (size_t)c * EPL;
     }
     uint4 kv[kAttnUnroll], vv[kAttnUnroll];
 #pragma unroll
-    for (int u = 0; u < kAttnUnroll; ++u) kv[u] = *reinterpret_cast<const uint4*>(Kp + off[u]);
+    for (int u = 0; u < kAttnUnroll; ++u)
+      kv[u] = *reinterpret_cast<const uint4*>((RB && in_rb[u] ? Kr : Kp) + off[u]);
 #pragma unroll
-    for (int u = 0; u < kAttnUnroll; ++u) vv[u] = *reinterpret_cast<const uint4*>(Vp + off[u]);
+    for (int u = 0; u < kAttnUnroll; ++u)
+      vv[u] = *reinterpret_cast<const uint4*>((RB && in_rb[u] ? Vr : Vp) + off[u]);
 
     // logits (already in log2 units) of this slot's token against each head
     float z[kAttnUnroll][QPK];
@@ -240,28 +254,34 @@ namespace {
 template <typename E, int D, int QPK>
 hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                           const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                          void* out, int* arrivals, hipStream_t st) {
+                          void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
   using S = typename E::storage;
   int log2G = 0;
   while ((1 << log2G) < p.group_size) ++log2G;
   const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
-  hipLaunchKernelGGL((attn_partial_kernel<E, D, QPK>), grid, block, 0, st, (const S*)q, (const S*)K,
-                     (const S*)V, idx, part_ml, part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, p.ctx_len,
-                     p.n_select, log2G,
-                     pl.attn_units, pl.attn_units_per_split, pl.attn_splits, scale * kLog2e);
+  // units of the whole attended-token list: the selected tokens, then the rolling buffer
+  const int units = (p.n_select * p.group_size + rb.len + pl.kv_toks_per_unit - 1) / pl.kv_toks_per_unit;
+  auto launch = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
+                       part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
+                       p.n_select, log2G, units, pl.attn_units_per_split, pl.attn_splits,
+                       scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity);
+  };
+  if (rb.len > 0) launch(attn_partial_kernel<E, D, QPK, true>);
+  else launch(attn_partial_kernel<E, D, QPK, false>);
   return hipGetLastError();
 }
 
 template <typename E, int D>
 hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                       const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                      void* out, int* arrivals, hipStream_t st) {
+                      void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
   switch (pl.q_per_kv) {
-    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
-    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
-    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
-    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
   }
   return hipErrorInvalidValue;
 }
@@ -269,10 +289,10 @@ hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const 
 template <typename E>
 hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                     const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                    void* out, int* arrivals, hipStream_t st) {
+                    void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
   switch (p.head_dim) {
-    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
-    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
   }
   return hipErrorInvalidValue;
 }
@@ -281,9 +301,9 @@ hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const vo
 
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       void* out, int* arrivals, hipStream_t st) {
-  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
-  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, st);
+                       void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
+  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
 }
 
 }  // namespace kvs

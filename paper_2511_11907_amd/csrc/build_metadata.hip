@@ -23,12 +23,13 @@ constexpr int kMetaRows = 64;
 template <typename EK, typename EM, int RC>  // RC = r / 4 output columns per lane
 __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     const typename EK::storage* __restrict__ K, const float* __restrict__ A,
-    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int heads_per_set, int N, int d) {
+    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int heads_per_set, int ctx_rows,
+    int first_row, int row_end, int d) {
   constexpr int R = RC * 4;
   extern __shared__ float s_k[];  // [kMetaRows][d + 1]
   const int tid = threadIdx.x;
   const int set = blockIdx.y;  // (b, k), or b alone when the heads are projected jointly
-  const int row0 = blockIdx.x * kMetaRows;
+  const int row0 = first_row + blockIdx.x * kMetaRows;  // rows [first_row, row_end) are built
   const int ld = d + 1;
   constexpr int EPL = EK::kPerLane;
   const int lanes_per_row = d / EPL;
@@ -43,11 +44,11 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     const int k = p % n_kv_heads;
     if (kk > 0) lds_barrier();               // everyone is done with the previous tile
     // stage the tile: 16 bytes per lane, consecutive lanes along the row
-    const typename EK::storage* Kp = K + ((size_t)p * N + row0) * d;
+    const typename EK::storage* Kp = K + ((size_t)p * ctx_rows + row0) * d;
     for (int i = tid; i < kMetaRows * lanes_per_row; i += kMetaThreads) {
       const int r_ = i / lanes_per_row, cc = i % lanes_per_row;
       float f[EPL];
-      if (row0 + r_ < N) {
+      if (row0 + r_ < row_end) {
         const uint4 v = *reinterpret_cast<const uint4*>(Kp + (size_t)r_ * d + (size_t)cc * EPL);
         unpack16<EK>(v, f);
       } else {
@@ -65,8 +66,8 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
       for (int j = 0; j < RC; ++j) acc[j] = fmaf(kv, Ak[(size_t)i * R + j], acc[j]);
     }
   }
-  if (row0 + row < N) {
-    typename EM::storage* o = K_lr + ((size_t)set * N + row0 + row) * R + (size_t)jq * RC;
+  if (row0 + row < row_end) {
+    typename EM::storage* o = K_lr + ((size_t)set * ctx_rows + row0 + row) * R + (size_t)jq * RC;
 #pragma unroll
     for (int j = 0; j < RC; ++j) {
       if constexpr (EM::kBytes == 2) o[j] = float_to_bf16_bits(acc[j]);
@@ -79,23 +80,23 @@ namespace {
 
 template <typename EK, typename EM, int RC>
 hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* K, const float* A,
-                      void* K_lr, hipStream_t st) {
-  dim3 grid((p.ctx_len + kMetaRows - 1) / kMetaRows, pl.sets), block(kMetaThreads);
+                      void* K_lr, int first_row, int n_rows, hipStream_t st) {
+  dim3 grid((n_rows + kMetaRows - 1) / kMetaRows, pl.sets), block(kMetaThreads);
   const size_t lds = (size_t)kMetaRows * (p.head_dim + 1) * sizeof(float);
   hipLaunchKernelGGL((build_metadata_kernel<EK, EM, RC>), grid, block, lds, st,
                      (const typename EK::storage*)K, A, (typename EM::storage*)K_lr, p.n_kv_heads,
-                     pl.kv_heads_per_set, p.ctx_len, p.head_dim);
+                     pl.kv_heads_per_set, pl.ctx_rows, first_row, first_row + n_rows, p.head_dim);
   return hipGetLastError();
 }
 
 template <typename EK, typename EM>
 hipError_t launch_r(const kvs_params& p, const Plan& pl, const void* K, const float* A,
-                    void* K_lr, hipStream_t st) {
+                    void* K_lr, int first_row, int n_rows, hipStream_t st) {
   switch (p.rank) {
-    case 16: return launch_one<EK, EM, 4>(p, pl, K, A, K_lr, st);
-    case 32: return launch_one<EK, EM, 8>(p, pl, K, A, K_lr, st);
-    case 64: return launch_one<EK, EM, 16>(p, pl, K, A, K_lr, st);
-    case 128: return launch_one<EK, EM, 32>(p, pl, K, A, K_lr, st);
+    case 16: return launch_one<EK, EM, 4>(p, pl, K, A, K_lr, first_row, n_rows, st);
+    case 32: return launch_one<EK, EM, 8>(p, pl, K, A, K_lr, first_row, n_rows, st);
+    case 64: return launch_one<EK, EM, 16>(p, pl, K, A, K_lr, first_row, n_rows, st);
+    case 128: return launch_one<EK, EM, 32>(p, pl, K, A, K_lr, first_row, n_rows, st);
   }
   return hipErrorInvalidValue;
 }
@@ -103,12 +104,39 @@ hipError_t launch_r(const kvs_params& p, const Plan& pl, const void* K, const fl
 }  // namespace
 
 hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void* K,
-                                 const float* A, void* K_lr, hipStream_t st) {
+                                 const float* A, void* K_lr, int first_row, int n_rows,
+                                 hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
   const bool kb = p.kv_dtype == KVS_BF16, mb = p.meta_dtype == KVS_BF16;
-  if (kb && mb) return launch_r<BF16Elem, BF16Elem>(p, pl, K, A, K_lr, st);
-  if (kb && !mb) return launch_r<BF16Elem, F32Elem>(p, pl, K, A, K_lr, st);
-  if (!kb && mb) return launch_r<F32Elem, BF16Elem>(p, pl, K, A, K_lr, st);
-  return launch_r<F32Elem, F32Elem>(p, pl, K, A, K_lr, st);
+  if (kb && mb) return launch_r<BF16Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+  if (kb && !mb) return launch_r<BF16Elem, F32Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+  if (!kb && mb) return launch_r<F32Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+  return launch_r<F32Elem, F32Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+}
+
+// A completed group leaves the rolling buffer (Sec. 3.4.1): the first G rows of every
+// (b, kv head)'s buffer become cache rows N .. N+G-1.  16 bytes per lane, one workgroup
+// per problem (G*d elements of K and of V: a few KiB).
+__global__ __launch_bounds__(256) void append_rows_kernel(const uint4* __restrict__ rb_K,
+                                                          const uint4* __restrict__ rb_V,
+                                                          uint4* __restrict__ K, uint4* __restrict__ V,
+                                                          size_t rb_stride16, size_t cache_stride16,
+                                                          size_t dst_off16, int n16) {
+  const size_t p = blockIdx.x;
+  for (int i = threadIdx.x; i < n16; i += blockDim.x) {
+    K[p * cache_stride16 + dst_off16 + i] = rb_K[p * rb_stride16 + i];
+    V[p * cache_stride16 + dst_off16 + i] = rb_V[p * rb_stride16 + i];
+  }
+}
+
+hipError_t launch_append_rows(const kvs_params& p, const Plan& pl, const RollingBuffer& rb,
+                              void* K, void* V, hipStream_t st) {
+  const size_t row16 = (size_t)p.head_dim * (p.kv_dtype == KVS_BF16 ? 2 : 4) / 16;  // 16-byte pieces per row
+  hipLaunchKernelGGL(append_rows_kernel, dim3(pl.problems), dim3(256), 0, st, (const uint4*)rb.K,
+                     (const uint4*)rb.V, (uint4*)K, (uint4*)V, (size_t)rb.capacity * row16,
+                     (size_t)pl.ctx_rows * row16, (size_t)p.ctx_len * row16,
+                     (int)(p.group_size * row16));
+  return hipGetLastError();
 }
 
 }  // namespace kvs

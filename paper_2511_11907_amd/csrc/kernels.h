@@ -21,10 +21,21 @@ constexpr int kJointMaxFlatDim = 4096;          // H_kv * d the query projection
 
 // Launch geometry derived from the params alone (the host computes it once per
 // call; kvs_workspace_bytes uses the same numbers).
+// The newest tokens of every (b, kv head), kept outside the cache until they form a
+// group (Sec. 3.4.1): K, V [B, H_kv, capacity, d], the first `len` rows valid.
+struct RollingBuffer {
+  const void* K = nullptr;
+  const void* V = nullptr;
+  int len = 0;
+  int capacity = 0;
+};
+constexpr int kRollingBufferMaxLen = 256;
+
 struct Plan {
   int problems;          // P = B * H_kv: attention problems
   int sets;              // selection sets: P, or B in joint-head mode (one K_lr, one idx each)
   int kv_heads_per_set;  // 1, or H_kv in joint-head mode
+  int ctx_rows;          // rows held per problem by K, V and K_lr (>= N)
   int n_groups;          // NG = N / G
   int q_per_kv;          // H_q / H_kv
   // predict
@@ -46,8 +57,13 @@ struct Plan {
 
 Plan make_plan(const kvs_params& p);
 
+// rows [first_row, first_row + n_rows) of every selection set
 hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void* K,
-                                 const float* A, void* K_lr, hipStream_t st);
+                                 const float* A, void* K_lr, int first_row, int n_rows,
+                                 hipStream_t st);
+// cache rows [N, N + G) of every (b, kv head) <- the first G rows of its rolling buffer
+hipError_t launch_append_rows(const kvs_params& p, const Plan& pl, const RollingBuffer& rb,
+                              void* K, void* V, hipStream_t st);
 // hist == nullptr: scores only.  Otherwise the kernel also adds the histogram of the top
 // 12 key bits of every score to `hist` (kSelectHistBins ints per problem, zero on entry).
 // qlr: joint-head mode only (nullptr otherwise): pl.sets * r floats of scratch that receive
@@ -60,7 +76,7 @@ hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int
                        int* hist, hipStream_t st);
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       void* out, int* arrivals, hipStream_t st);
+                       void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 }  // namespace kvs

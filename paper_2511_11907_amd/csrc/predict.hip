@@ -45,7 +45,7 @@ template <typename E, int R, int G, bool HIST>
 __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     const void* __restrict__ q, int q_is_bf16, const typename E::storage* __restrict__ K_lr,
     const float* __restrict__ A, float* gs, int n_kv_heads, int q_per_kv, int d,
-    int N, int units, int units_per_wg, int mean, int* __restrict__ hist,
+    int N, int ctx_rows, int units, int units_per_wg, int mean, int* __restrict__ hist,
     const float* __restrict__ qlr) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPR = R / EPL;          // lanes per row
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   const int c = lane % LPR;   // 16-byte column of the row
   const int rl = lane / LPR;  // row within the unit
 
-  const typename E::storage* Kp = K_lr + (size_t)p * N * R;
+  const typename E::storage* Kp = K_lr + (size_t)p * ctx_rows * R;
   float* gsp = gs + (size_t)p * (N / G);
   const int u0 = blockIdx.x * units_per_wg;
   const int u1 = min(units, u0 + units_per_wg);
@@ -269,12 +269,12 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const 
   if (hist)
     hipLaunchKernelGGL((predict_kernel<E, R, G, true>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
-                       p.head_dim, p.ctx_len, pl.predict_units, pl.predict_units_per_wg, mean, hist,
+                       p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean, hist,
                        (const float*)qlr);
   else
     hipLaunchKernelGGL((predict_kernel<E, R, G, false>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
-                       p.head_dim, p.ctx_len, pl.predict_units, pl.predict_units_per_wg, mean,
+                       p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean,
                        (int*)nullptr, (const float*)qlr);
   return hipGetLastError();
 }

@@ -138,6 +138,36 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert s(ctypes.byref(c), fake, fake, fake, fake, fake, fake, null, fake, fake, 64, null) == E_WS
 
 
+def test_rolling_buffer_capacity_and_append_arguments_are_checked_on_the_host():
+    lib = kv.load_library()
+    fake, odd, null = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x10004), ctypes.c_void_p(0)
+    big = 1 << 30
+    assert kv.kvs_check_params(_p(ctx_capacity=32768 + 64)) == OK
+    assert kv.kvs_check_params(_p(ctx_capacity=32000)) == E_SHAPE           # capacity < ctx_len
+    assert kv.kvs_check_params(_p(ctx_capacity=1 << 24)) == E_UNSUP         # capacity * d >= 2^31
+    c = _p(ctx_capacity=32768 + 8)._c()
+    a = lib.kvs_sparse_decode_attn_rb
+    args = lambda rk, rv, n, cap: (ctypes.byref(c), fake, fake, fake, fake, rk, rv, n, cap, fake, fake, big, null)
+    assert a(*args(null, null, 3, 4)) == E_NULL                             # tokens but no buffer
+    assert a(*args(fake, fake, 5, 4)) == E_SHAPE                            # rb_len > capacity
+    assert a(*args(fake, fake, -1, 4)) == E_SHAPE
+    assert a(*args(fake, odd, 2, 4)) == E_ALIGN
+    assert a(*args(fake, fake, 300, 512)) == E_UNSUP                        # rb_len > 256
+    s = lib.kvs_decode_step_rb
+    assert s(ctypes.byref(c), fake, fake, fake, fake, fake, null, null, 2, 4, fake, null, fake, fake, big, null) == E_NULL
+    assert s(ctypes.byref(c), fake, fake, fake, fake, fake, fake, fake, 9, 4, fake, null, fake, fake, big, null) == E_SHAPE
+    g = lib.kvs_append_group
+    assert g(ctypes.byref(c), null, fake, 4, fake, fake, fake, fake, null) == E_NULL
+    assert g(ctypes.byref(c), fake, fake, 3, fake, fake, fake, fake, null) == E_SHAPE      # buffer < one group
+    full = _p()._c()                                                                       # no spare rows
+    assert g(ctypes.byref(full), fake, fake, 4, fake, fake, fake, fake, null) == E_SHAPE
+    assert g(ctypes.byref(c), fake, odd, 4, fake, fake, fake, fake, null) == E_ALIGN
+    r = lib.kvs_build_metadata_rows
+    assert r(ctypes.byref(c), fake, fake, fake, 32768, 16, null) == E_SHAPE                # leaves the capacity
+    assert r(ctypes.byref(c), fake, fake, fake, -1, 4, null) == E_SHAPE
+    assert r(ctypes.byref(c), null, fake, fake, 0, 4, null) == E_NULL
+
+
 def test_binding_refuses_host_tensors():
     torch = pytest.importorskip("torch")
     p = _p(ctx_len=64, n_select=2)
