@@ -15,7 +15,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 REDUCE_MAX, REDUCE_MEAN = 0, 1
 HEADS_SEPARATE, HEADS_JOINT = 0, 1
 
@@ -27,7 +27,7 @@ class _Params(ctypes.Structure):
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32),
         ("reduce", ctypes.c_int32), ("head_mode", ctypes.c_int32), ("ctx_capacity", ctypes.c_int32),
-        ("n_threads", ctypes.c_int32),
+        ("n_threads", ctypes.c_int32), ("meta_scale", ctypes.c_double),
         ("softmax_scale", ctypes.c_double),
     ]
 
@@ -49,12 +49,13 @@ class Shape:
     softmax_scale: float = 0.0
     head_mode: int = HEADS_SEPARATE
     ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
+    meta_scale: float = 0.0    # K_lr is stored divided by this (0: 1)
 
     def _c(self) -> _Params:
         return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                        self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
                        self.meta_dtype, self.reduce, self.head_mode, self.ctx_capacity,
-                       self.n_threads, self.softmax_scale)
+                       self.n_threads, self.meta_scale, self.softmax_scale)
 
     @property
     def rows(self) -> int:
@@ -91,6 +92,10 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_dense_attn.argtypes = [pp, vp, vp, vp, vp]
         _lib.oracle_round_to_bf16.argtypes = [ctypes.c_double]
         _lib.oracle_round_to_bf16.restype = ctypes.c_uint16
+        _lib.oracle_round_to_fp8_e4m3.argtypes = [ctypes.c_double]
+        _lib.oracle_round_to_fp8_e4m3.restype = ctypes.c_uint8
+        _lib.oracle_fp8_e4m3_value.argtypes = [ctypes.c_uint8]
+        _lib.oracle_fp8_e4m3_value.restype = ctypes.c_double
         for f in (_lib.oracle_build_metadata, _lib.oracle_predict_select, _lib.oracle_sparse_attn,
                   _lib.oracle_dense_attn, _lib.oracle_sparse_attn_rb, _lib.oracle_build_metadata_rows):
             f.restype = ctypes.c_int
@@ -98,7 +103,7 @@ def lib() -> ctypes.CDLL:
 
 
 def _np_dtype(code: int):
-    return np.float32 if code == F32 else np.uint16
+    return {F32: np.float32, BF16: np.uint16, FP8_E4M3: np.uint8}[code]
 
 
 def _arr(x, dtype, shape, name):
@@ -204,3 +209,11 @@ def dense_attn(sh: Shape, q, K, V):
 
 def round_to_bf16(x: float) -> int:
     return int(lib().oracle_round_to_bf16(float(x)))
+
+
+def round_to_fp8_e4m3(x: float) -> int:
+    return int(lib().oracle_round_to_fp8_e4m3(float(x)))
+
+
+def fp8_e4m3_value(code: int) -> float:
+    return float(lib().oracle_fp8_e4m3_value(int(code)))

@@ -12,8 +12,45 @@
 
 /* ---- storage access ----------------------------------------------------- */
 
+/* Value of an 8-bit float code, OCP "E4M3" (finite-only variant): 1 sign, 4 exponent
+ * (bias 7), 3 mantissa bits; exponent 0 is subnormal (m/8 * 2^-6); the code with all
+ * exponent and mantissa bits set is NaN; there are no infinities; largest value 448. */
+double oracle_fp8_e4m3_value(uint8_t code) {
+  const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m / 8.0, -6);
+  else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return sign ? -v : v;
+}
+
+/* Nearest finite E4M3 code to x, ties to the even mantissa, magnitudes beyond the
+ * largest value saturate to +-448 (NaN -> the NaN code). */
+uint8_t oracle_round_to_fp8_e4m3(double x) {
+  if (isnan(x)) return 0x7F;
+  const uint8_t sign = signbit(x) ? 0x80 : 0x00;
+  double a = fabs(x);
+  if (a >= 448.0) return sign | 0x7E;
+  /* spacing of the format at a: 2^-9 below 2^-6 (subnormals and the first binade share
+   * it), else 2^(floor(log2 a) - 3) */
+  int e;
+  (void)frexp(a, &e);                 /* a = f * 2^e, f in [0.5, 1) => floor(log2 a) = e-1 */
+  int ulp_exp = (e - 1) - 3;
+  if (ulp_exp < -9) ulp_exp = -9;
+  double steps = nearbyint(ldexp(a, -ulp_exp)); /* nearest-even in the default mode */
+  double y = ldexp(steps, ulp_exp);             /* a value of the format (may be 2^k of the next binade) */
+  if (y == 0.0) return sign;
+  (void)frexp(y, &e);
+  int be = (e - 1) + 7;                         /* biased exponent */
+  uint8_t code;
+  if (be <= 0) code = (uint8_t)nearbyint(ldexp(y, 9)); /* subnormal: y = m * 2^-9 */
+  else code = (uint8_t)((be << 3) | (int)nearbyint((ldexp(y, -(e - 1)) - 1.0) * 8.0));
+  return sign | code;
+}
+
 static double load_elem(const void* base, int dtype, size_t i) {
   if (dtype == ORC_F32) return (double)((const float*)base)[i];
+  if (dtype == ORC_FP8_E4M3) return oracle_fp8_e4m3_value(((const uint8_t*)base)[i]);
   uint32_t bits = (uint32_t)((const uint16_t*)base)[i] << 16; /* bf16 = top half of fp32 */
   float f;
   memcpy(&f, &bits, sizeof f);
@@ -44,8 +81,13 @@ uint16_t oracle_round_to_bf16(double x) {
 
 static void store_meta(void* base, int dtype, size_t i, double x) {
   if (dtype == ORC_F32) ((float*)base)[i] = (float)x; /* C conversion: nearest-even */
+  else if (dtype == ORC_FP8_E4M3) ((uint8_t*)base)[i] = oracle_round_to_fp8_e4m3(x);
   else ((uint16_t*)base)[i] = oracle_round_to_bf16(x);
 }
+
+/* The metadata is stored divided by meta_scale (so that it fits the range of a narrow
+ * dtype) and multiplied back when it is read. */
+static double meta_scale(const orc_params* p) { return p->meta_scale != 0.0 ? p->meta_scale : 1.0; }
 
 static int params_ok(const orc_params* p) {
   if (!p) return 0;
@@ -55,7 +97,9 @@ static int params_ok(const orc_params* p) {
   if (p->n_q_heads % p->n_kv_heads) return 0;
   if (p->ctx_len % p->group_size) return 0;
   if (p->kv_dtype != ORC_F32 && p->kv_dtype != ORC_BF16) return 0;
-  if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16) return 0;
+  if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16 && p->meta_dtype != ORC_FP8_E4M3)
+    return 0;
+  if (!(p->meta_scale >= 0.0) || isinf(p->meta_scale)) return 0;
   if (p->head_mode != ORC_HEADS_SEPARATE && p->head_mode != ORC_HEADS_JOINT) return 0;
   if (p->ctx_capacity != 0 && p->ctx_capacity < p->ctx_len) return 0;
   return 1;
@@ -87,7 +131,7 @@ static int build_metadata_joint(const orc_params* p, const void* K, const float*
             acc += load_elem(K, p->kv_dtype, krow + i) * (double)A[((size_t)k * d + i) * r + j];
         }
         if (K_lr_exact) K_lr_exact[orow + j] = acc;
-        store_meta(K_lr, p->meta_dtype, orow + j, acc);
+        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p));
       }
     }
   }
@@ -118,7 +162,7 @@ int oracle_build_metadata_rows(const orc_params* p, const void* K, const float* 
         for (int i = 0; i < d; ++i)
           acc += load_elem(K, p->kv_dtype, krow + i) * (double)Ak[(size_t)i * r + j];
         if (K_lr_exact) K_lr_exact[orow + j] = acc;
-        store_meta(K_lr, p->meta_dtype, orow + j, acc);
+        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p));
       }
     }
   }
@@ -217,7 +261,7 @@ static int predict_select_joint(const orc_params* p, const void* q, const void* 
       for (int h = 0; h < Hq; ++h) {
         double acc = 0.0;
         for (int j = 0; j < r; ++j)
-          acc += q_lr[(size_t)h * r + j] * load_elem(K_lr, p->meta_dtype, row + j);
+          acc += q_lr[(size_t)h * r + j] * (meta_scale(p) * load_elem(K_lr, p->meta_dtype, row + j));
         tot += acc;
       }
       s[n] = tot;
@@ -273,7 +317,7 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
       for (int hh = 0; hh < qpk; ++hh) {
         double acc = 0.0;
         for (int j = 0; j < r; ++j)
-          acc += q_lr[(size_t)hh * r + j] * load_elem(K_lr, p->meta_dtype, row + j);
+          acc += q_lr[(size_t)hh * r + j] * (meta_scale(p) * load_elem(K_lr, p->meta_dtype, row + j));
         tot += acc;
       }
       s[n] = tot;

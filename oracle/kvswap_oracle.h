@@ -27,7 +27,11 @@
  * Rolling buffer (Sec. 3.4.1 "New KV entries management"): the newest tokens, not yet
  * a complete group, live outside the cache in rb_K, rb_V [B, H_kv, rb_capacity, d]
  * (first rb_len rows valid); they are never scored and always attended.
- * Storage dtypes: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns).  Stored
+ * Metadata precision (Sec. 3.2: the compressed K cache only ranks tokens, so its precision
+ * may be traded for memory): meta_dtype may also be 8-bit floating point (OCP E4M3,
+ * uint8 codes), and K_lr is stored as round(K.A / meta_scale) and read back as
+ * meta_scale * stored (meta_scale 0 => 1; it applies to every meta_dtype).
+ * Storage dtypes: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns), 2 = fp8 E4M3 (uint8).  Stored
  * values are widened to fp64 exactly; every sum is an fp64 sum in natural
  * index order.
  *
@@ -44,6 +48,9 @@
  * output; all groups + buffer equals dense attention over the concatenated cache;
  * padded (capacity > ctx_len) arrays with poisoned padding give the compact results;
  * metadata of a row range equals the same rows of the full build.
+ * fp8: every code's value and the rounding of many values against the float8 type of a
+ * tensor library and against a nearest-neighbour search over all codes; hand-derived
+ * ties and saturation; the whole path against brute force on the decoded values.
  * The paper prints no worked numeric example of this path, so numeric parity
  * with the authors' own implementation is unpinned (parity unpinned on that
  * point only; every function below has the pins listed above).
@@ -57,7 +64,7 @@
 extern "C" {
 #endif
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_FP8_E4M3 = 2 /* meta_dtype only */ };
 enum { ORC_REDUCE_MAX = 0, ORC_REDUCE_MEAN = 1 };
 enum { ORC_HEADS_SEPARATE = 0, ORC_HEADS_JOINT = 1 };
 
@@ -69,6 +76,7 @@ typedef struct {
   int32_t head_mode;                                    /* ORC_HEADS_*        */
   int32_t ctx_capacity; /* rows allocated per problem in K, V, K_lr; 0 => ctx_len      */
   int32_t n_threads;   /* OpenMP threads over the (b, kv head) problems; <=1: serial */
+  double meta_scale;   /* K_lr is stored divided by this; 0 => 1 */
   double softmax_scale; /* 0 => 1/sqrt(d) */
 } orc_params;
 
@@ -122,6 +130,9 @@ int oracle_dense_attn(const orc_params* p, const void* q, const void* K,
 /* fp64 -> storage dtype rounding used by oracle_build_metadata (exposed so the
  * tests can pin it against hand-derived values). */
 uint16_t oracle_round_to_bf16(double x);
+/* the same for the 8-bit E4M3 format: nearest-even, saturating at +-448 */
+uint8_t oracle_round_to_fp8_e4m3(double x);
+double oracle_fp8_e4m3_value(uint8_t code);
 
 #ifdef __cplusplus
 }
