@@ -35,14 +35,15 @@ CACHE_BYTES = 256e6 + 32e6     # last-level cache + the eight L2s
 # --------------------------------------------------------------------------------------
 # algorithmic bytes: what the method itself has to move per layer-step
 # --------------------------------------------------------------------------------------
-def algorithmic_bytes(cfg) -> dict:
+def algorithmic_bytes(cfg, meta_bytes: int = None) -> dict:
+    """meta_bytes: bytes per element of K_lr (default: those of the workload's dtype)."""
     P = cfg.batch * cfg.n_kv_heads
     S = cfg.batch if cfg.joint else P      # selection sets: one K_lr, one score row, one idx each
     eb = cfg.elem_bytes
     NG, M = cfg.n_groups, cfg.n_select
     q_bytes = cfg.batch * cfg.n_q_heads * cfg.head_dim * eb
     a_bytes = cfg.n_kv_heads * cfg.head_dim * cfg.rank * 4
-    predict = S * cfg.ctx_len * cfg.rank * eb + q_bytes + a_bytes + S * NG * 4
+    predict = S * cfg.ctx_len * cfg.rank * (meta_bytes or eb) + q_bytes + a_bytes + S * NG * 4
     topk = S * NG * 4 + S * M * 4
     attn = S * M * 4 + 2 * P * M * cfg.group_size * cfg.head_dim * eb + q_bytes + q_bytes
     return {"predict": predict, "topk": topk, "attn": attn, "step": predict + topk + attn}
@@ -52,7 +53,7 @@ def algorithmic_bytes(cfg) -> dict:
 # workload: device-resident rotating copies
 # --------------------------------------------------------------------------------------
 class Workload:
-    def __init__(self, cfg, copies: int, log=print):
+    def __init__(self, cfg, copies: int, log=print, meta: str = None):
         import torch
         import paper_2511_11907_amd as kv
         from workloads import make_layer
@@ -61,8 +62,10 @@ class Workload:
         dev = "cuda:0"
         code = kv.KVS_F32 if cfg.dtype == "f32" else kv.KVS_BF16
         tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        # 8-bit metadata: stored as K.A / 8 so that the heavy hitters stay inside the format
+        mcode, mscale, mdt = (kv.KVS_FP8_E4M3, 0.125, torch.float8_e4m3fn) if meta == "fp8" else (code, 0.0, tdt)
         self.p = kv.Params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank,
-                           cfg.ctx_len, cfg.group_size, cfg.n_select, code, code,
+                           cfg.ctx_len, cfg.group_size, cfg.n_select, code, mcode, meta_scale=mscale,
                            head_mode=kv.KVS_HEADS_JOINT if cfg.joint else kv.KVS_HEADS_SEPARATE)
         self.ws = torch.empty(kv.kvs_workspace_bytes(self.p) // 4, dtype=torch.float32, device=dev)
         kv.kvs_workspace_init(self.p, self.ws)
@@ -90,7 +93,7 @@ class Workload:
                 A0 = L.A
             s = {"K": up(L.K), "V": up(L.V), "q": up(L.q), "A": up(L.A)}
             sets = self.p.sets
-            s["K_lr"] = torch.empty(sets + (N, cfg.rank), dtype=tdt, device=dev)
+            s["K_lr"] = torch.empty(sets + (N, cfg.rank), dtype=mdt, device=dev)
             kv.kvs_build_metadata(self.p, s["K"], s["A"], s["K_lr"])
             s["idx"] = torch.empty(sets + (cfg.n_select,), dtype=torch.int32, device=dev)
             s["gs"] = torch.empty(sets + (cfg.n_groups,), dtype=torch.float32, device=dev)
@@ -250,7 +253,7 @@ def load_traffic(cfg_name: str, kernel: str):
         return None
 
 
-def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
+def cpu_baseline(cfg, L, budget_s: float = 12.0, meta: str = None) -> dict:
     """The fp64 oracle as it stands, single-threaded, on the same inputs: whole steps
     (prediction + selection + sparse attention) of copy 0 until ~budget_s seconds."""
     import numpy as np
@@ -260,8 +263,9 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
     # bound the sample: at most 8 (sequence, kv head) problems of the batch
     P = cfg.batch * cfg.n_kv_heads
     nb = max(1, min(cfg.batch, 8 // cfg.n_kv_heads if cfg.n_kv_heads <= 8 else 1))
+    mcode, mscale = (oracle.FP8_E4M3, 0.125) if meta == "fp8" else (code, 0.0)
     sh = oracle.Shape(nb, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rank, cfg.ctx_len,
-                      cfg.group_size, cfg.n_select, code, code, n_threads=1,
+                      cfg.group_size, cfg.n_select, code, mcode, n_threads=1, meta_scale=mscale,
                       head_mode=oracle.HEADS_JOINT if cfg.joint else oracle.HEADS_SEPARATE)
     K, V, q = (np.ascontiguousarray(x[:nb]) for x in (L.K, L.V, L.q))
     klr = oracle.build_metadata(oracle.Shape(**{**sh.__dict__, "n_threads": 8}), K, L.A)  # untimed set-up
@@ -281,12 +285,12 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0) -> dict:
                       f"({frac:.3g} of a full layer-step); value scaled to all {cfg.layers} layer(s)"}
 
 
-def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> dict:
-    ab = algorithmic_bytes(cfg)
+def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, meta=None) -> dict:
+    ab = algorithmic_bytes(cfg, 1 if meta == "fp8" else None)
     if copies is None:
         copies = max(2, int(-(-3 * CACHE_BYTES // ab["step"])))   # rotation >= 3x the caches
         copies = min(copies, 32)
-    wl = Workload(cfg, copies, log)
+    wl = Workload(cfg, copies, log, meta)
     sec = time_steps(wl, steps, warmup, mode)
     ms_step = sec / steps * 1e3
     layers = wl.layers_per_step
@@ -321,7 +325,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True) -> 
                         "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if want_cpu:
-        res["cpu_baseline"] = cpu_baseline(cfg, wl.host0)
+        res["cpu_baseline"] = cpu_baseline(cfg, wl.host0, meta=meta)
     del wl, one
     import torch
     torch.cuda.empty_cache()
@@ -339,6 +343,8 @@ def main() -> int:
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--copies", type=int, default=None, help="rotating input copies (default: 3x the caches)")
     ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
+    ap.add_argument("--meta", default="same", choices=["same", "fp8"],
+                    help="dtype of the compressed K cache: that of the workload, or 8-bit E4M3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one 256 MiB device copy (calibration kernel for rocprofv3 --pmc byte counters)")
@@ -367,13 +373,14 @@ def main() -> int:
         del src, dst
 
     cfg = PRESETS[args.config]
+    meta = None if args.meta == "same" else args.meta
     main_res = measure(cfg, args.steps, args.warmup, args.mode, args.copies, log,
-                       want_cpu=not args.no_cpu_baseline)
+                       want_cpu=not args.no_cpu_baseline, meta=meta)
     others = {}
     for name in [x for x in args.extra.split(",") if x and x != args.config]:
         c = PRESETS[name]
         st = max(20, min(args.steps, 60))
-        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False)
+        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta)
         others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
                                           "roofline", "copies", "layer_ahead")}
         others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
@@ -395,7 +402,8 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv d={cfg.head_dim} "
                                f"N={cfg.ctx_len} b={cfg.batch} r={cfg.rank} G={cfg.group_size} "
                                f"M={cfg.n_select} layers={cfg.layers} {cfg.dtype}"
-                               + (" joint-head" if cfg.joint else ""),
+                               + (" joint-head" if cfg.joint else "")
+                               + (" fp8-metadata" if meta else ""),
                    "mode": args.mode, "input_copies": main_res["copies"]},
         "step_hbm_gbps": main_res["step_gbps"],
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,

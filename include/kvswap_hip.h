@@ -23,6 +23,12 @@
  * The full K/V cache lives in device memory (it stands in for the paper's disk
  * tier plus preload buffer).
  *
+ * Metadata precision (Sec. 3.2: the compressed K cache only ranks tokens, so its
+ * precision may be traded for memory): meta_dtype may be fp32, bf16 or the 8-bit float
+ * OCP E4M3 (finite-only, largest value 448; one byte per element, which halves the
+ * stream of the prediction again).  K_lr is stored as round(K.A / meta_scale), nearest
+ * even, saturating for E4M3; scores use meta_scale * stored.
+ *
  * Memory: every pointer below is a DEVICE pointer unless it says "host".  All
  * tensors are contiguous and row-major, 16-byte aligned:
  *   K, V          [B, H_kv, N, d]   kv_dtype      (a group = G consecutive rows,
@@ -89,7 +95,7 @@ typedef enum {
   KVS_ERR_ALIGN = 7        /* a tensor pointer is not 16-byte aligned         */
 } kvs_status;
 
-typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
+typedef enum { KVS_F32 = 0, KVS_BF16 = 1, KVS_FP8_E4M3 = 2 /* meta_dtype only */ } kvs_dtype;
 typedef enum { KVS_REDUCE_MAX = 0, KVS_REDUCE_MEAN = 1 } kvs_reduce;
 typedef enum { KVS_HEADS_SEPARATE = 0, KVS_HEADS_JOINT = 1 } kvs_head_mode;
 
@@ -101,6 +107,8 @@ typedef struct {
   int32_t reduce;        /* kvs_reduce; MAX is the paper's ReduceMax                   */
   float softmax_scale;   /* 0 => 1/sqrt(d)                                             */
   int32_t head_mode;     /* kvs_head_mode; SEPARATE (0) = one adapter per KV head      */
+  float meta_scale;      /* K_lr is stored divided by this and multiplied back when it is
+                            scored (0 => 1): fits the metadata to a narrow meta_dtype     */
   int32_t ctx_capacity;  /* rows allocated per (b, kv head) in K and V, and per selection
                             set in K_lr; 0 => ctx_len.  Rows ctx_len .. capacity-1 are room
                             for the groups a decode loop appends and are never read.       */

@@ -5,7 +5,7 @@ marshalling only, every step of the path runs in the library's kernels.  There
 is no CPU fallback; a missing or unloadable library raises.
 """
 from .binding import (  # noqa: F401
-    KVS_F32, KVS_BF16, KVS_REDUCE_MAX, KVS_REDUCE_MEAN, KVS_HEADS_SEPARATE, KVS_HEADS_JOINT,
+    KVS_F32, KVS_BF16, KVS_FP8_E4M3, KVS_REDUCE_MAX, KVS_REDUCE_MEAN, KVS_HEADS_SEPARATE, KVS_HEADS_JOINT,
     KvsError, Params, load_library, library_path,
     kvs_check_params, kvs_workspace_bytes, kvs_workspace_init, kvs_status_str, kvs_version, kvs_last_device_error,
     kvs_build_metadata, kvs_build_metadata_rows, kvs_append_group,

@@ -13,7 +13,7 @@ from dataclasses import dataclass
 
 from . import build as _build
 
-KVS_F32, KVS_BF16 = 0, 1
+KVS_F32, KVS_BF16, KVS_FP8_E4M3 = 0, 1, 2
 KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
 KVS_HEADS_SEPARATE, KVS_HEADS_JOINT = 0, 1
 
@@ -40,7 +40,7 @@ class _CParams(ctypes.Structure):
         ("ctx_len", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_select", ctypes.c_int32),
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32), ("reduce", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float), ("head_mode", ctypes.c_int32),
-        ("ctx_capacity", ctypes.c_int32),
+        ("meta_scale", ctypes.c_float), ("ctx_capacity", ctypes.c_int32),
     ]
 
 
@@ -60,12 +60,13 @@ class Params:
     softmax_scale: float = 0.0
     head_mode: int = KVS_HEADS_SEPARATE
     ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
+    meta_scale: float = 0.0    # K_lr is stored divided by this (0: 1)
 
     def _c(self) -> _CParams:
         return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                         self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
                         self.meta_dtype, self.reduce, self.softmax_scale, self.head_mode,
-                        self.ctx_capacity)
+                        self.meta_scale, self.ctx_capacity)
 
     @property
     def rows(self) -> int:
@@ -150,7 +151,7 @@ def _torch():
 
 def _dtype_of(code: int):
     torch = _torch()
-    return torch.float32 if code == KVS_F32 else torch.bfloat16
+    return {KVS_F32: torch.float32, KVS_BF16: torch.bfloat16, KVS_FP8_E4M3: torch.float8_e4m3fn}[code]
 
 
 def _dev(t, dtype, shape, name):

@@ -45,7 +45,7 @@ Plan make_plan(const kvs_params& p) {
 
   // predict: one resident wave of workgroups over the whole chip, each streaming at
   // least one full step of its 16 waves
-  const int meta_epl = p.meta_dtype == KVS_BF16 ? 8 : 4;
+  const int meta_epl = p.meta_dtype == KVS_FP8_E4M3 ? 16 : (p.meta_dtype == KVS_BF16 ? 8 : 4);
   pl.meta_lanes_per_row = p.rank / meta_epl;
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;
   pl.predict_units = ceil_div(p.ctx_len, pl.meta_rows_per_unit);
@@ -98,7 +98,7 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
       p->ctx_len < 1 || p->group_size < 1)
     return KVS_ERR_SHAPE;
   if ((p->kv_dtype != KVS_F32 && p->kv_dtype != KVS_BF16) ||
-      (p->meta_dtype != KVS_F32 && p->meta_dtype != KVS_BF16) ||
+      (p->meta_dtype != KVS_F32 && p->meta_dtype != KVS_BF16 && p->meta_dtype != KVS_FP8_E4M3) ||
       (p->reduce != KVS_REDUCE_MAX && p->reduce != KVS_REDUCE_MEAN) ||
       (p->head_mode != KVS_HEADS_SEPARATE && p->head_mode != KVS_HEADS_JOINT))
     return KVS_ERR_DTYPE;
@@ -108,6 +108,7 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
   const bool joint = p->head_mode == KVS_HEADS_JOINT;
   if (p->rank > (joint ? p->n_kv_heads : 1) * p->head_dim) return KVS_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return KVS_ERR_SHAPE;
+  if (!(p->meta_scale >= 0.f) || isinf(p->meta_scale)) return KVS_ERR_SHAPE;
   const int ng = p->ctx_len / p->group_size;
   if (need_select && (p->n_select < 1 || p->n_select > ng)) return KVS_ERR_SHAPE;
   // supported set

@@ -24,7 +24,7 @@ template <typename EK, typename EM, int RC>  // RC = r / 4 output columns per la
 __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     const typename EK::storage* __restrict__ K, const float* __restrict__ A,
     typename EM::storage* __restrict__ K_lr, int n_kv_heads, int heads_per_set, int ctx_rows,
-    int first_row, int row_end, int d) {
+    int first_row, int row_end, int d, float meta_scale) {
   constexpr int R = RC * 4;
   extern __shared__ float s_k[];  // [kMetaRows][d + 1]
   const int tid = threadIdx.x;
@@ -70,8 +70,10 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     typename EM::storage* o = K_lr + ((size_t)set * ctx_rows + row0 + row) * R + (size_t)jq * RC;
 #pragma unroll
     for (int j = 0; j < RC; ++j) {
-      if constexpr (EM::kBytes == 2) o[j] = float_to_bf16_bits(acc[j]);
-      else o[j] = acc[j];
+      const float v = acc[j] / meta_scale;  // (exact when the scale is 1)
+      if constexpr (EM::kBytes == 2) o[j] = float_to_bf16_bits(v);
+      else if constexpr (EM::kBytes == 1) o[j] = float_to_fp8_e4m3(v);
+      else o[j] = v;
     }
   }
 }
@@ -85,7 +87,8 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* K, const 
   const size_t lds = (size_t)kMetaRows * (p.head_dim + 1) * sizeof(float);
   hipLaunchKernelGGL((build_metadata_kernel<EK, EM, RC>), grid, block, lds, st,
                      (const typename EK::storage*)K, A, (typename EM::storage*)K_lr, p.n_kv_heads,
-                     pl.kv_heads_per_set, pl.ctx_rows, first_row, first_row + n_rows, p.head_dim);
+                     pl.kv_heads_per_set, pl.ctx_rows, first_row, first_row + n_rows, p.head_dim,
+                     p.meta_scale != 0.f ? p.meta_scale : 1.0f);
   return hipGetLastError();
 }
 
@@ -108,6 +111,10 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
                                  hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;
   const bool kb = p.kv_dtype == KVS_BF16, mb = p.meta_dtype == KVS_BF16;
+  if (p.meta_dtype == KVS_FP8_E4M3) {
+    if (kb) return launch_r<BF16Elem, FP8Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+    return launch_r<F32Elem, FP8Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
+  }
   if (kb && mb) return launch_r<BF16Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
   if (kb && !mb) return launch_r<BF16Elem, F32Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
   if (!kb && mb) return launch_r<F32Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);

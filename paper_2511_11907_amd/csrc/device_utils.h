@@ -9,7 +9,7 @@ namespace kvs {
 constexpr int kWave = 64;
 
 // ---- storage element traits ------------------------------------------------
-// A lane always moves 16 bytes per load: 4 fp32 or 8 bf16 values.
+// A lane always moves 16 bytes per load: 4 fp32, 8 bf16 or 16 fp8 values.
 struct F32Elem {
   using storage = float;
   static constexpr int kBytes = 4;
@@ -19,6 +19,14 @@ struct BF16Elem {
   using storage = uint16_t;
   static constexpr int kBytes = 2;
   static constexpr int kPerLane = 8;
+};
+
+// 8-bit float, OCP E4M3 (finite-only): metadata only.  gfx950's packed conversions
+// implement exactly this format (checked on the device for all 256 codes).
+struct FP8Elem {
+  using storage = uint8_t;
+  static constexpr int kBytes = 1;
+  static constexpr int kPerLane = 16;
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
@@ -54,6 +62,27 @@ __device__ __forceinline__ void unpack16<BF16Elem>(const uint4& v, float (&f)[8]
   f[5] = __uint_as_float(v.z & 0xFFFF0000u);
   f[6] = __uint_as_float(v.w << 16);
   f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+template <>
+__device__ __forceinline__ void unpack16<FP8Elem>(const uint4& v, float (&f)[16]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {  // bytes 0,1 and 2,3 of each dword, two values per conversion
+    const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+    const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+    f[4 * i + 0] = lo[0];
+    f[4 * i + 1] = lo[1];
+    f[4 * i + 2] = hi[0];
+    f[4 * i + 3] = hi[1];
+  }
+}
+
+// fp32 -> E4M3 code, round-to-nearest-even, magnitudes beyond 448 saturate (the
+// hardware conversion would turn them into NaN).
+__device__ __forceinline__ uint8_t float_to_fp8_e4m3(float x) {
+  const float c = fminf(fmaxf(x, -448.0f), 448.0f);
+  return (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(c, c, 0, false) & 0xFF);
 }
 
 // Scalar load of one stored element as fp32 (runtime dtype; cold paths only).

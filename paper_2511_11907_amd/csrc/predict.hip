@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     const void* __restrict__ q, int q_is_bf16, const typename E::storage* __restrict__ K_lr,
     const float* __restrict__ A, float* gs, int n_kv_heads, int q_per_kv, int d,
     int N, int ctx_rows, int units, int units_per_wg, int mean, int* __restrict__ hist,
-    const float* __restrict__ qlr) {
+    const float* __restrict__ qlr, float meta_scale) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPR = R / EPL;          // lanes per row
   constexpr int RPU = kWave / LPR;      // rows per unit
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
       a_reg[i] = Ak[(size_t)min(psl * span + i, d - 1) * R + pj];  // rows past the span are never used
   } else {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qr[e] = qlr[(size_t)p * R + c * EPL + e];
+    for (int e = 0; e < EPL; ++e) qr[e] = qlr[(size_t)p * R + c * EPL + e] * meta_scale;
   }
   int ub = u0;  // base of the current workgroup step
   if (ub < u1) issue(ub);
@@ -143,7 +143,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     }
     lds_barrier();
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qr[e] = s_qlr[c * EPL + e];
+    // the stored metadata is K.A / meta_scale: the factor goes into the query once
+    for (int e = 0; e < EPL; ++e) qr[e] = s_qlr[c * EPL + e] * meta_scale;
   } else if constexpr (HIST) {
     lds_barrier();  // the histogram is cleared before anyone counts into it
   }
@@ -260,6 +261,7 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const 
                       const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
   dim3 grid(pl.predict_chunks, pl.sets), block(kPredictThreads);
   const int q_bf16 = (int)(p.kv_dtype == KVS_BF16), mean = (int)(p.reduce == KVS_REDUCE_MEAN);
+  const float scale = p.meta_scale != 0.f ? p.meta_scale : 1.0f;
   if (qlr) {
     hipLaunchKernelGGL((project_query_kernel<R>), dim3(pl.sets), dim3(kProjectThreads), 0, st, q,
                        q_bf16, A, qlr, p.n_kv_heads, pl.q_per_kv, p.head_dim);
@@ -270,12 +272,12 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const 
     hipLaunchKernelGGL((predict_kernel<E, R, G, true>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
                        p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean, hist,
-                       (const float*)qlr);
+                       (const float*)qlr, scale);
   else
     hipLaunchKernelGGL((predict_kernel<E, R, G, false>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
                        p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean,
-                       (int*)nullptr, (const float*)qlr);
+                       (int*)nullptr, (const float*)qlr, scale);
   return hipGetLastError();
 }
 
@@ -309,6 +311,7 @@ hipError_t launch_r(const kvs_params& p, const Plan& pl, const void* q, const vo
 hipError_t launch_predict(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
                           const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
   if (p.meta_dtype == KVS_BF16) return launch_r<BF16Elem>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+  if (p.meta_dtype == KVS_FP8_E4M3) return launch_r<FP8Elem>(p, pl, q, K_lr, A, gs, hist, qlr, st);
   return launch_r<F32Elem>(p, pl, q, K_lr, A, gs, hist, qlr, st);
 }
 

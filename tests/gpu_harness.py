@@ -18,19 +18,33 @@ MARGIN = 1e-4                            # relative margin of the index rule
 
 
 def dt_code(name: str) -> int:
-    return kv.KVS_F32 if name == "f32" else kv.KVS_BF16
+    return {"f32": kv.KVS_F32, "bf16": kv.KVS_BF16, "fp8": kv.KVS_FP8_E4M3}[name]
+
+
+_FP8_VALUES = np.array([oracle.fp8_e4m3_value(c) for c in range(256)])
+
+
+def meta_values(x: np.ndarray) -> np.ndarray:
+    """Stored metadata (float32, uint16 bf16 bits or uint8 E4M3 codes) -> fp64 values."""
+    if x.dtype == np.uint8:
+        return _FP8_VALUES[x]
+    return storage_to_f32(x).astype(np.float64)
 
 
 def to_dev(x: np.ndarray) -> torch.Tensor:
     """Storage array (float32, uint16 bf16 bits, int32) -> device tensor."""
     if x.dtype == np.uint16:
         return torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
+    if x.dtype == np.uint8:
+        return torch.from_numpy(np.ascontiguousarray(x)).to(DEV).view(torch.float8_e4m3fn)
     return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
 
 
 def to_host_storage(t: torch.Tensor) -> np.ndarray:
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    if t.dtype == torch.float8_e4m3fn:
+        return t.view(torch.uint8).cpu().numpy()
     return t.cpu().numpy()
 
 
@@ -41,6 +55,8 @@ def kv_params(cfg: Config, **over) -> kv.Params:
              kv_dtype=dt_code(cfg.dtype), meta_dtype=dt_code(cfg.dtype),
              head_mode=kv.KVS_HEADS_JOINT if cfg.joint else kv.KVS_HEADS_SEPARATE)
     d.update(over)
+    if isinstance(d["meta_dtype"], str):
+        d["meta_dtype"] = dt_code(d["meta_dtype"])
     return kv.Params(**d)
 
 
@@ -52,6 +68,8 @@ def orc_shape(cfg: Config, n_threads: int = 8, **over) -> oracle.Shape:
              n_threads=n_threads,
              head_mode=oracle.HEADS_JOINT if cfg.joint else oracle.HEADS_SEPARATE)
     d.update(over)
+    if isinstance(d["meta_dtype"], str):
+        d["meta_dtype"] = {"f32": oracle.F32, "bf16": oracle.BF16, "fp8": oracle.FP8_E4M3}[d["meta_dtype"]]
     return oracle.Shape(**d)
 
 
@@ -108,28 +126,32 @@ def out_values(t: torch.Tensor) -> np.ndarray:
 
 
 # ---- one full comparison of a small configuration --------------------------------------
-def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bool = True):
+def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bool = True,
+                    meta: str = None, meta_scale: float = 0.0):
     """Whole path at a size the oracle finishes in seconds: metadata, prediction and
-    selection, attention with the oracle's indices, and the fused decode step."""
+    selection, attention with the oracle's indices, and the fused decode step.
+    `meta` overrides the metadata dtype ("f32", "bf16", "fp8")."""
     L = make_layer(cfg, layer)
     D = DeviceLayer(L)
-    p = kv_params(cfg, reduce=reduce)
-    sh = orc_shape(cfg, reduce=reduce)
+    meta = meta or cfg.dtype
+    p = kv_params(cfg, reduce=reduce, meta_dtype=meta, meta_scale=meta_scale)
+    sh = orc_shape(cfg, reduce=reduce, meta_dtype=meta, meta_scale=meta_scale)
     B, Hk, N, r, M = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.n_select
     stats = {}
 
     # metadata: oracle-rounded K_lr is the reference and the input of the next step
     klr_ref, klr_exact = oracle.build_metadata(sh, L.K, L.A, want_exact=True)
     if check_meta:
-        klr_gpu = torch.empty(p.sets + (N, r), dtype=D.K.dtype, device=DEV)
+        klr_gpu = torch.empty(p.sets + (N, r), dtype=to_dev(klr_ref[..., :1, :]).dtype, device=DEV)
         kv.kvs_build_metadata(p, D.K, D.A, klr_gpu)
         torch.cuda.synchronize()
         # joint-head mode contracts over the H_kv*d flattened key row
         absdot = np.einsum("bknd,kdr->bnr" if cfg.joint else "bknd,kdr->bknr",
                            np.abs(storage_to_f32(L.K)).astype(np.float64), np.abs(L.A).astype(np.float64))
         terms = cfg.head_dim * (Hk if cfg.joint else 1)
-        stats["meta_mismatch"] = compare_metadata(to_host_storage(klr_gpu), klr_ref, klr_exact,
-                                                  absdot, terms, cfg.dtype)
+        sc = meta_scale or 1.0        # stored units: K.A / meta_scale
+        stats["meta_mismatch"] = compare_metadata(to_host_storage(klr_gpu), klr_ref, klr_exact / sc,
+                                                  absdot / sc, terms, meta)
 
     ws = workspace(p)
     klr_dev = to_dev(klr_ref)
@@ -171,10 +193,71 @@ def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bo
     return stats
 
 
+# ---- full-size configurations, oracle on sampled problems ------------------------------------
+def full_size_sampled(cfg: Config, samples, budgets=None, layer=0, meta: str = None,
+                      meta_scale: float = 0.0):
+    """GPU on the whole batch at the real size; oracle on the sampled (b, k) problems.
+    The metadata of the sampled problems is built by the oracle and written over the
+    GPU-built rows, so both sides score exactly the same K_lr."""
+    L = make_layer(cfg, layer, workers=16)
+    D = DeviceLayer(L)
+    meta = meta or cfg.dtype
+    mk = dict(meta_dtype=meta, meta_scale=meta_scale)
+    sc = meta_scale or 1.0
+    p = kv_params(cfg, **mk)
+    B, Hk, N, r, qpk = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.q_per_kv
+    klr = torch.empty((B, Hk, N, r), dtype=kv.binding._dtype_of(p.meta_dtype), device=DEV)
+    kv.kvs_build_metadata(p, D.K, D.A, klr)
+    torch.cuda.synchronize()
+    sub = {}
+    for (b, k) in samples:
+        sh1 = orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk, **mk)
+        K1, V1 = L.K[b:b + 1, k:k + 1], L.V[b:b + 1, k:k + 1]
+        q1, A1 = L.q[b:b + 1, k * qpk:(k + 1) * qpk], L.A[k:k + 1]
+        klr1, exact1 = oracle.build_metadata(sh1, K1, A1, want_exact=True)
+        absdot = np.abs(storage_to_f32(K1)).astype(np.float64)[0, 0] @ np.abs(A1[0]).astype(np.float64)
+        frac = compare_metadata(to_host_storage(klr[b, k]), klr1[0, 0], exact1[0, 0] / sc, absdot / sc,
+                                cfg.head_dim, meta)
+        klr[b, k].copy_(to_dev(klr1[0, 0]))
+        sub[(b, k)] = (sh1, K1, V1, q1, A1, klr1, frac)
+    results = {}
+    for M in (budgets or [cfg.n_select]):
+        pM = kv_params(cfg, n_select=M, **mk)
+        ws = workspace(pM)
+        idx = torch.full((B, Hk, M), -1, dtype=torch.int32, device=DEV)
+        out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=D.q.dtype, device=DEV)
+        kv.kvs_decode_step(pM, D.q, klr, D.A, D.K, D.V, idx, None, out, ws)
+        torch.cuda.synchronize()
+        idx_h, out_h = idx.cpu().numpy(), out_values(out)
+        # properties that hold for every problem at any size
+        assert np.all(np.diff(idx_h, axis=-1) > 0) and idx_h.min() >= 0 and idx_h.max() < cfg.n_groups
+        assert np.isfinite(out_h).all()
+        worst = 0.0
+        for (b, k), (sh1, K1, V1, q1, A1, klr1, frac) in sub.items():
+            shM = orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk, n_select=M, **mk)
+            ref = oracle.predict_select(shM, q1, klr1, A1)
+            check_index_margin(idx_h[b, k], ref["gs"][0, 0], ref["boundary"][0, 0], f"{cfg.name} M={M} b={b} k={k}")
+            out_ref = oracle.sparse_attn(shM, q1, K1, V1, idx_h[b:b + 1, k:k + 1])
+            err = attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], out_ref)
+            assert err <= ATTN_TOL[cfg.dtype], (cfg.name, M, b, k, err)
+            if M == cfg.n_groups:   # 100 % budget: the step is dense attention
+                dense = oracle.dense_attn(shM, q1, K1, V1)
+                assert attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], dense) <= ATTN_TOL[cfg.dtype]
+            worst = max(worst, err)
+        results[M] = worst
+    print(f"[parity] {cfg.name}_full meta={meta}: " + ", ".join(f"M={m}: {e:.3g}" for m, e in results.items()),
+          flush=True)
+    return results
+
+
+
 def _ulp(v: np.ndarray, dtype: str) -> np.ndarray:
-    """Spacing of the storage dtype at |v| (normal range)."""
+    """Spacing of the storage dtype at |v| (normal range; E4M3 also below it)."""
     if dtype == "f32":
         return np.spacing(np.abs(v).astype(np.float32)).astype(np.float64)
+    if dtype == "fp8":
+        e = np.floor(np.log2(np.maximum(np.abs(v), 2.0 ** -6)))
+        return 2.0 ** (e - 3)
     e = np.floor(np.log2(np.maximum(np.abs(v), 2.0 ** -126)))
     return 2.0 ** (e - 7)
 
@@ -187,13 +270,15 @@ def compare_metadata(klr_gpu: np.ndarray, klr_ref: np.ndarray, klr_exact: np.nda
     storage the result must also be bit-identical to the oracle's rounding except where the
     exact value sits that close to a rounding boundary (a fraction of a per cent).
     Returns the fraction of elements that differ from the oracle's rounded array."""
-    g = storage_to_f32(klr_gpu).astype(np.float64)
-    r = storage_to_f32(klr_ref).astype(np.float64)
-    acc = d * 2.0 ** -24 * absdot
+    g = meta_values(klr_gpu)
+    r = meta_values(klr_ref)
+    if dtype == "fp8":     # saturating format: compare against the clamped exact value
+        klr_exact = np.clip(klr_exact, -448.0, 448.0)
+    acc = (d + 2) * 2.0 ** -24 * absdot      # fp32 accumulation, plus the division by the scale
     ulp = np.maximum(_ulp(g, dtype), _ulp(klr_exact, dtype))
     assert np.all(np.abs(g - klr_exact) <= 0.5 * ulp + acc + 1e-300), \
         "GPU metadata is further from the exact product than rounding + fp32 accumulation allow"
     frac = float((g != r).mean())
-    if dtype == "bf16":
+    if dtype in ("bf16", "fp8"):
         assert frac <= 2e-3, f"too many metadata elements differ from the oracle: {frac}"
     return frac

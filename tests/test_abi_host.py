@@ -73,6 +73,13 @@ def _p(**kw):
     (dict(head_mode=1, n_kv_heads=1, n_q_heads=4, rank=128, head_dim=64), E_SHAPE),
     (dict(head_mode=1, n_kv_heads=64, n_q_heads=64), E_UNSUP),  # H_kv*d > 4096
     (dict(head_mode=2), E_DTYPE),
+    # 8-bit metadata, metadata scale
+    (dict(meta_dtype=2), OK),
+    (dict(meta_dtype=2, meta_scale=0.125, rank=16), OK),
+    (dict(kv_dtype=2), E_DTYPE),              # keys and values are not stored in 8 bits
+    (dict(meta_dtype=3), E_DTYPE),
+    (dict(meta_scale=-0.5), E_SHAPE),
+    (dict(meta_scale=float("inf")), E_SHAPE),
 ])
 def test_check_params(kw, code):
     assert kv.kvs_check_params(_p(**kw)) == code

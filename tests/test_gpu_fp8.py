@@ -1,0 +1,75 @@
+"""GPU parity of the 8-bit (E4M3) compressed K cache and of the metadata scale (Sec. 3.2:
+the metadata only ranks tokens, so its precision may be traded for memory) against the
+CPU oracle, through the C-ABI binding."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_11907_amd as kv
+import gpu_harness as H
+from workloads import PRESETS, Config, make_layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the GPU (run them with -m gpu on a GPU box)")
+    kv.load_library()
+
+
+def _say(name, stats):
+    print(f"[parity] {name}: " + ", ".join(f"{k}={v:.3g}" if isinstance(v, float) else f"{k}={v}"
+                                           for k, v in stats.items()), flush=True)
+
+
+def _variant(name, dtype, Hq, Hk, d, r, G, N, M, B=2, joint=False):
+    return Config(name, 1, B, Hq, Hk, d, N, r, G, M, dtype, min(r, 32), 0.1, 8, joint=joint)
+
+
+CASES = [
+    # (config, metadata scale): every row-width class of the 8-bit layout (1, 2, 4, 8 lanes
+    # per row), groups inside one load and across two, both head modes, both KV dtypes
+    (PRESETS["c2"].replace(name="c2s_fp8", batch=2, ctx_len=4096, n_select=103), 0.125),
+    (PRESETS["c2"].replace(name="c2r_fp8", batch=1, ctx_len=4004, n_select=77), 0.0),
+    (PRESETS["c4"].replace(name="c4s_fp8", batch=1, ctx_len=16384, n_select=256), 0.0625),
+    (PRESETS["c2j"].replace(name="c2js_fp8", batch=2, ctx_len=4096, n_select=103), 0.25),
+    (_variant("bf16_r16_g1_fp8", "bf16", 4, 2, 64, 16, 1, 2048, 100), 0.1),
+    (_variant("bf16_r128_g16_fp8", "bf16", 8, 1, 128, 128, 16, 2048, 9), 0.05),
+    (_variant("f32_r64_g2_fp8", "f32", 4, 2, 64, 64, 2, 1536, 50), 0.2),
+    (_variant("f32_r128_g8_joint_fp8", "f32", 8, 4, 64, 128, 8, 2048, 17, joint=True), 0.5),
+    # a scale so small that many products leave the format's range: both sides saturate alike
+    (_variant("bf16_r32_g4_saturating_fp8", "bf16", 8, 2, 128, 32, 4, 2048, 40), 1.0 / 256),
+]
+
+
+@pytest.mark.parametrize("cfg,scale", CASES, ids=[c[0].name for c in CASES])
+def test_fp8_metadata_matches_the_oracle(cfg, scale):
+    stats = H.run_and_compare(cfg, meta="fp8", meta_scale=scale)
+    _say(cfg.name, stats)
+
+
+def test_scale_applies_to_wider_metadata_too():
+    cfg = PRESETS["c2"].replace(name="c2s_scaled_bf16", batch=2, ctx_len=4096, n_select=103)
+    _say(cfg.name, H.run_and_compare(cfg, meta="bf16", meta_scale=0.37))
+    _say(cfg.name + "_f32meta", H.run_and_compare(cfg, meta="f32", meta_scale=3.0))
+
+
+def test_fp8_metadata_with_mean_reduce_and_rolling_capacity():
+    cfg = PRESETS["c2"].replace(name="c2s_fp8_mean", batch=2, ctx_len=4096, n_select=103)
+    _say(cfg.name, H.run_and_compare(cfg, reduce=kv.KVS_REDUCE_MEAN, meta="fp8", meta_scale=0.125))
+
+
+def test_c3_full_size_fp8_sampled():
+    H.full_size_sampled(PRESETS["c3"], [(0, 1), (5, 6)], meta="fp8", meta_scale=0.125)
+
+
+def test_c4_full_size_fp8_sampled():
+    H.full_size_sampled(PRESETS["c4"], [(2, 3)], meta="fp8", meta_scale=0.125)
+
+
+def test_fp8_is_refused_for_keys_and_values():
+    p = H.kv_params(PRESETS["c2"], kv_dtype=kv.KVS_FP8_E4M3)
+    assert kv.kvs_check_params(p) == 3

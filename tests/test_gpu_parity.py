@@ -288,54 +288,7 @@ def test_uninitialised_histogram_cannot_write_out_of_bounds():
 
 
 # ---- full-size configurations, oracle on sampled problems ------------------------------------------
-def _full_size_sampled(cfg: Config, samples, budgets=None, layer=0):
-    """GPU on the whole batch at the real size; oracle on the sampled (b, k) problems.
-    The metadata of the sampled problems is built by the oracle and written over the
-    GPU-built rows, so both sides score exactly the same K_lr."""
-    L = make_layer(cfg, layer, workers=16)
-    D = H.DeviceLayer(L)
-    p = H.kv_params(cfg)
-    B, Hk, N, r, qpk = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.q_per_kv
-    klr = torch.empty((B, Hk, N, r), dtype=D.K.dtype, device=H.DEV)
-    kv.kvs_build_metadata(p, D.K, D.A, klr)
-    torch.cuda.synchronize()
-    sub = {}
-    for (b, k) in samples:
-        sh1 = H.orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk)
-        K1, V1 = L.K[b:b + 1, k:k + 1], L.V[b:b + 1, k:k + 1]
-        q1, A1 = L.q[b:b + 1, k * qpk:(k + 1) * qpk], L.A[k:k + 1]
-        klr1, exact1 = oracle.build_metadata(sh1, K1, A1, want_exact=True)
-        absdot = np.abs(storage_to_f32(K1)).astype(np.float64)[0, 0] @ np.abs(A1[0]).astype(np.float64)
-        frac = H.compare_metadata(H.to_host_storage(klr[b, k]), klr1[0, 0], exact1[0, 0], absdot,
-                                  cfg.head_dim, cfg.dtype)
-        klr[b, k].copy_(H.to_dev(klr1[0, 0]))
-        sub[(b, k)] = (sh1, K1, V1, q1, A1, klr1, frac)
-    results = {}
-    for M in (budgets or [cfg.n_select]):
-        pM = H.kv_params(cfg, n_select=M)
-        ws = H.workspace(pM)
-        idx = torch.full((B, Hk, M), -1, dtype=torch.int32, device=H.DEV)
-        out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=D.q.dtype, device=H.DEV)
-        kv.kvs_decode_step(pM, D.q, klr, D.A, D.K, D.V, idx, None, out, ws)
-        torch.cuda.synchronize()
-        idx_h, out_h = idx.cpu().numpy(), H.out_values(out)
-        # properties that hold for every problem at any size
-        assert np.all(np.diff(idx_h, axis=-1) > 0) and idx_h.min() >= 0 and idx_h.max() < cfg.n_groups
-        assert np.isfinite(out_h).all()
-        worst = 0.0
-        for (b, k), (sh1, K1, V1, q1, A1, klr1, frac) in sub.items():
-            shM = H.orc_shape(cfg, batch=1, n_kv_heads=1, n_q_heads=qpk, n_select=M)
-            ref = oracle.predict_select(shM, q1, klr1, A1)
-            H.check_index_margin(idx_h[b, k], ref["gs"][0, 0], ref["boundary"][0, 0], f"{cfg.name} M={M} b={b} k={k}")
-            out_ref = oracle.sparse_attn(shM, q1, K1, V1, idx_h[b:b + 1, k:k + 1])
-            err = H.attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], out_ref)
-            assert err <= H.ATTN_TOL[cfg.dtype], (cfg.name, M, b, k, err)
-            if M == cfg.n_groups:   # 100 % budget: the step is dense attention
-                dense = oracle.dense_attn(shM, q1, K1, V1)
-                assert H.attn_error(out_h[b:b + 1, k * qpk:(k + 1) * qpk], dense) <= H.ATTN_TOL[cfg.dtype]
-            worst = max(worst, err)
-        results[M] = worst
-    _say(cfg.name + "_full", {f"M={m}": e for m, e in results.items()})
+_full_size_sampled = H.full_size_sampled
 
 
 def test_c2_full_size_sampled():
