@@ -316,7 +316,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
         "dominant": dom,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": load_traffic(cfg.name, dom),
+                     "traffic": load_traffic(cfg.name, dom) if meta is None else None,
                      "algorithmic_bytes": ab[dom], "kernel_us": kern[dom]},
         "algorithmic_bytes": ab,
         "copies": len(wl.slots),

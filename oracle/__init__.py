@@ -89,6 +89,10 @@ def lib() -> ctypes.CDLL:
         i32 = ctypes.c_int32
         _lib.oracle_sparse_attn_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i32, vp]
         _lib.oracle_build_metadata_rows.argtypes = [pp, vp, vp, vp, vp, i32, i32]
+        _lib.oracle_sparse_attn_paged.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+        _lib.oracle_selection_overlap.argtypes = [pp, vp, vp, vp]
+        _lib.oracle_sparse_attn_paged.restype = ctypes.c_int
+        _lib.oracle_selection_overlap.restype = ctypes.c_int
         _lib.oracle_dense_attn.argtypes = [pp, vp, vp, vp, vp]
         _lib.oracle_round_to_bf16.argtypes = [ctypes.c_double]
         _lib.oracle_round_to_bf16.restype = ctypes.c_uint16
@@ -192,6 +196,42 @@ def sparse_attn(sh: Shape, q, K, V, idx, rb_K=None, rb_V=None, rb_len: int = 0):
     _check(lib().oracle_sparse_attn_rb(ctypes.byref(c), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
                                        _ptr(rb_K), _ptr(rb_V), int(rb_len), int(cap), _ptr(out)),
            "oracle_sparse_attn_rb")
+    return out
+
+
+def sparse_attn_paged(sh: Shape, q, K_pool, V_pool, slot_table, idx, rb_K=None, rb_V=None, rb_len: int = 0):
+    """Attention over the selected groups read through a mapping table: K_pool, V_pool
+    [n_slots, G, d], slot_table [B, H_kv, NG] int32 (logical group -> slot)."""
+    q = _arr(q, _np_dtype(sh.kv_dtype), (sh.batch, sh.n_q_heads, sh.head_dim), "q")
+    n_slots = K_pool.shape[0]
+    shape_pool = (n_slots, sh.group_size, sh.head_dim)
+    K_pool = _arr(K_pool, _np_dtype(sh.kv_dtype), shape_pool, "K_pool")
+    V_pool = _arr(V_pool, _np_dtype(sh.kv_dtype), shape_pool, "V_pool")
+    slot_table = _arr(slot_table, np.int32, (sh.batch, sh.n_kv_heads, sh.n_groups), "slot_table")
+    idx = _arr(idx, np.int32, sh.sets + (sh.n_select,), "idx")
+    out = np.empty((sh.batch, sh.n_q_heads, sh.head_dim), dtype=np.float64)
+    cap = 0
+    if rb_K is not None:
+        cap = rb_K.shape[2]
+        shape_rb = (sh.batch, sh.n_kv_heads, cap, sh.head_dim)
+        rb_K = _arr(rb_K, _np_dtype(sh.kv_dtype), shape_rb, "rb_K")
+        rb_V = _arr(rb_V, _np_dtype(sh.kv_dtype), shape_rb, "rb_V")
+    c = sh._c()
+    _check(lib().oracle_sparse_attn_paged(ctypes.byref(c), _ptr(q), _ptr(K_pool), _ptr(V_pool),
+                                          _ptr(slot_table), int(n_slots), _ptr(idx), _ptr(rb_K),
+                                          _ptr(rb_V), int(rb_len), int(cap), _ptr(out)),
+           "oracle_sparse_attn_paged")
+    return out
+
+
+def selection_overlap(sh: Shape, idx_prev, idx_cur):
+    """Number of groups common to two selections, per selection set (int32 array)."""
+    idx_prev = _arr(idx_prev, np.int32, sh.sets + (sh.n_select,), "idx_prev")
+    idx_cur = _arr(idx_cur, np.int32, sh.sets + (sh.n_select,), "idx_cur")
+    out = np.empty(sh.sets, dtype=np.int32)
+    c = sh._c()
+    _check(lib().oracle_selection_overlap(ctypes.byref(c), _ptr(idx_prev), _ptr(idx_cur), _ptr(out)),
+           "oracle_selection_overlap")
     return out
 
 

@@ -332,26 +332,27 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
 
 /* ---- attention ----------------------------------------------------------- */
 
-/* One softmax over the listed cache tokens of one (b, h) followed by the first rb_len
+/* One softmax over the listed tokens of one (b, h) followed by the first rb_len
  * rolling-buffer tokens of its KV head: out = sum_t w_t V_t / sum_t w_t with
- * w_t = exp(scale * q.K_t - max).  rb_K / rb_V may be NULL when rb_len is 0. */
-static int attend_tokens(const orc_params* p, const void* q, const void* K, const void* V,
-                         int b, int h, const int32_t* tokens, long n_tok, const void* rb_K,
-                         const void* rb_V, long rb_len, long rb_capacity, double scale,
-                         double* out) {
+ * w_t = exp(scale * q.K_t - max).  rows[t] is the index of the token's row in K and V
+ * counted in rows of d elements from the start of the arrays (the caller resolves cache
+ * position or mapping table); rb_K / rb_V may be NULL when rb_len is 0. */
+static int attend_rows(const orc_params* p, const void* q, const void* K, const void* V,
+                       int b, int h, const size_t* rows, long n_tok, const void* rb_K,
+                       const void* rb_V, long rb_len, long rb_capacity, double scale,
+                       double* out) {
   const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
   const int k = h / (Hq / Hk);
   const size_t qrow = ((size_t)b * Hq + h) * d;
-  const size_t kvbase = ((size_t)b * Hk + k) * row_capacity(p) * d;
   const size_t rbbase = ((size_t)b * Hk + k) * (size_t)rb_capacity * d;
   const long total = n_tok + rb_len;
   double* z = (double*)malloc(sizeof(double) * (size_t)total);
   if (!z) return -2;
   double zmax = -INFINITY;
   for (long t = 0; t < total; ++t) {
-    /* token t: a cache row, or (after all of those) a buffer row */
+    /* token t: a listed row, or (after all of those) a buffer row */
     const void* src = t < n_tok ? K : rb_K;
-    const size_t row = t < n_tok ? kvbase + (size_t)tokens[t] * d : rbbase + (size_t)(t - n_tok) * d;
+    const size_t row = t < n_tok ? rows[t] * d : rbbase + (size_t)(t - n_tok) * d;
     double acc = 0.0;
     for (int i = 0; i < d; ++i)
       acc += load_elem(q, p->kv_dtype, qrow + i) * load_elem(src, p->kv_dtype, row + i);
@@ -363,7 +364,7 @@ static int attend_tokens(const orc_params* p, const void* q, const void* K, cons
   for (long t = 0; t < total; ++t) {
     const double w = exp(z[t] - zmax);
     const void* src = t < n_tok ? V : rb_V;
-    const size_t row = t < n_tok ? kvbase + (size_t)tokens[t] * d : rbbase + (size_t)(t - n_tok) * d;
+    const size_t row = t < n_tok ? rows[t] * d : rbbase + (size_t)(t - n_tok) * d;
     denom += w;
     for (int i = 0; i < d; ++i) out[i] += w * load_elem(src, p->kv_dtype, row + i);
   }
@@ -401,14 +402,15 @@ int oracle_sparse_attn_rb(const orc_params* p, const void* q, const void* K, con
     const int b = (int)(bh / Hq), h = (int)(bh % Hq);
     const int k = h / (Hq / Hk);
     const int32_t* sel = idx + (joint ? (size_t)b : (size_t)b * Hk + k) * M;
-    int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)M * G);
-    if (!tokens) { failed = 1; continue; }
+    size_t* rows = (size_t*)malloc(sizeof(size_t) * (size_t)M * G);
+    if (!rows) { failed = 1; continue; }
+    const size_t base = ((size_t)b * Hk + k) * row_capacity(p); /* first row of this (b, kv head) */
     for (int m = 0; m < M; ++m)
-      for (int t = 0; t < G; ++t) tokens[(size_t)m * G + t] = sel[m] * G + t;
-    if (attend_tokens(p, q, K, V, b, h, tokens, (long)M * G, rb_K, rb_V, rb_len, rb_capacity,
-                      scale, out + (size_t)bh * d))
+      for (int t = 0; t < G; ++t) rows[(size_t)m * G + t] = base + (size_t)sel[m] * G + t;
+    if (attend_rows(p, q, K, V, b, h, rows, (long)M * G, rb_K, rb_V, rb_len, rb_capacity, scale,
+                    out + (size_t)bh * d))
       failed = 1;
-    free(tokens);
+    free(rows);
   }
   return failed ? -2 : 0;
 }
@@ -424,12 +426,71 @@ int oracle_dense_attn(const orc_params* p, const void* q, const void* K, const v
 #pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
   for (bh = 0; bh < BH; ++bh) {
     const int b = (int)(bh / Hq), h = (int)(bh % Hq);
-    int32_t* tokens = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
-    if (!tokens) { failed = 1; continue; }
-    for (int n = 0; n < N; ++n) tokens[n] = n;
-    if (attend_tokens(p, q, K, V, b, h, tokens, N, NULL, NULL, 0, 0, scale, out + (size_t)bh * d))
+    size_t* rows = (size_t*)malloc(sizeof(size_t) * (size_t)N);
+    if (!rows) { failed = 1; continue; }
+    const size_t base = ((size_t)b * p->n_kv_heads + h / (Hq / p->n_kv_heads)) * row_capacity(p);
+    for (int n = 0; n < N; ++n) rows[n] = base + (size_t)n;
+    if (attend_rows(p, q, K, V, b, h, rows, N, NULL, NULL, 0, 0, scale, out + (size_t)bh * d))
       failed = 1;
-    free(tokens);
+    free(rows);
   }
   return failed ? -2 : 0;
+}
+
+/* ---- mapping table (Sec. 3.4.3) and selection overlap (Sec. 3.4.2) --------- */
+
+int oracle_sparse_attn_paged(const orc_params* p, const void* q, const void* K_pool,
+                             const void* V_pool, const int32_t* slot_table, int32_t n_slots,
+                             const int32_t* idx, const void* rb_K, const void* rb_V,
+                             int32_t rb_len, int32_t rb_capacity, double* out) {
+  if (!params_ok(p) || !q || !K_pool || !V_pool || !slot_table || !idx || !out) return -1;
+  if (rb_len < 0 || rb_len > rb_capacity || (rb_len > 0 && (!rb_K || !rb_V))) return -1;
+  const int Hq = p->n_q_heads, Hk = p->n_kv_heads, d = p->head_dim;
+  const int G = p->group_size, M = p->n_select, NG = p->ctx_len / G;
+  if (M < 1 || M > NG || n_slots < 1) return -1;
+  const int joint = p->head_mode == ORC_HEADS_JOINT;
+  for (long i = 0; i < (long)p->batch * (joint ? 1 : Hk) * M; ++i)
+    if (idx[i] < 0 || idx[i] >= NG) return -1;
+  const double scale = resolve_scale(p);
+  const long BH = (long)p->batch * Hq;
+  int failed = 0, bad_slot = 0;
+  long bh;
+#pragma omp parallel for schedule(dynamic) num_threads(p->n_threads > 1 ? p->n_threads : 1)
+  for (bh = 0; bh < BH; ++bh) {
+    const int b = (int)(bh / Hq), h = (int)(bh % Hq);
+    const int k = h / (Hq / Hk);
+    const int32_t* sel = idx + (joint ? (size_t)b : (size_t)b * Hk + k) * M;
+    const int32_t* table = slot_table + ((size_t)b * Hk + k) * NG;
+    size_t* rows = (size_t*)malloc(sizeof(size_t) * (size_t)M * G);
+    if (!rows) { failed = 1; continue; }
+    int ok = 1;
+    for (int m = 0; m < M; ++m) {
+      const int32_t slot = table[sel[m]]; /* where logical group sel[m] physically is */
+      if (slot < 0 || slot >= n_slots) { ok = 0; break; }
+      for (int t = 0; t < G; ++t) rows[(size_t)m * G + t] = (size_t)slot * G + t;
+    }
+    if (!ok) bad_slot = 1;
+    else if (attend_rows(p, q, K_pool, V_pool, b, h, rows, (long)M * G, rb_K, rb_V, rb_len,
+                         rb_capacity, scale, out + (size_t)bh * d))
+      failed = 1;
+    free(rows);
+  }
+  if (bad_slot) return -1;
+  return failed ? -2 : 0;
+}
+
+int oracle_selection_overlap(const orc_params* p, const int32_t* idx_prev,
+                             const int32_t* idx_cur, int32_t* common) {
+  if (!params_ok(p) || !idx_prev || !idx_cur || !common) return -1;
+  const int M = p->n_select, NG = p->ctx_len / p->group_size;
+  if (M < 1 || M > NG) return -1;
+  const long sets = (long)p->batch * (p->head_mode == ORC_HEADS_JOINT ? 1 : p->n_kv_heads);
+  for (long s = 0; s < sets; ++s) {
+    int32_t n = 0;
+    for (int i = 0; i < M; ++i)     /* every pair: the definition, no ordering assumed */
+      for (int j = 0; j < M; ++j)
+        if (idx_cur[s * M + i] == idx_prev[s * M + j]) ++n;
+    common[s] = n;
+  }
+  return 0;
 }

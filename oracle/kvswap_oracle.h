@@ -48,6 +48,9 @@
  * output; all groups + buffer equals dense attention over the concatenated cache;
  * padded (capacity > ctx_len) arrays with poisoned padding give the compact results;
  * metadata of a row range equals the same rows of the full build.
+ * Mapping table: the identity table over the cache viewed as slots equals the unpaged
+ * call; a random permutation of the slots gives the same output; brute force over the
+ * gathered rows.  Overlap: numpy's intersect1d and hand cases.
  * fp8: every code's value and the rounding of many values against the float8 type of a
  * tensor library and against a nearest-neighbour search over all codes; hand-derived
  * ties and saturation; the whole path against brute force on the decoded values.
@@ -122,6 +125,25 @@ int oracle_sparse_attn_rb(const orc_params* p, const void* q, const void* K,
                           const void* V, const int32_t* idx, const void* rb_K,
                           const void* rb_V, int32_t rb_len, int32_t rb_capacity,
                           double* out);
+
+/* The same through a mapping table (Sec. 3.4.3 "KV cache manager": attention addresses
+ * its KV groups logically, a table maps them to where they physically are).  K_pool and
+ * V_pool are [n_slots, G, d]: slots of one group each, in any order and shared by all
+ * problems; slot_table [B, H_kv, NG] gives the slot of logical group j of (b, kv head).
+ * Group idx[m] of head h is read from slot slot_table[b, g(h), idx[m]].  The rolling
+ * buffer arguments are as in oracle_sparse_attn_rb.  Returns -1 for a slot outside
+ * [0, n_slots). */
+int oracle_sparse_attn_paged(const orc_params* p, const void* q, const void* K_pool,
+                             const void* V_pool, const int32_t* slot_table, int32_t n_slots,
+                             const int32_t* idx, const void* rb_K, const void* rb_V,
+                             int32_t rb_len, int32_t rb_capacity, double* out);
+
+/* Overlap of two selections (Sec. 3.4.2: the overlap ratio between consecutive steps
+ * that motivates reusing loaded groups): common[s] = number of group indices that occur
+ * in both idx_prev[s, :] and idx_cur[s, :], per selection set.  Each row must hold
+ * unique indices (any order). */
+int oracle_selection_overlap(const orc_params* p, const int32_t* idx_prev,
+                             const int32_t* idx_cur, int32_t* common);
 
 /* Ordinary softmax attention over all N tokens. */
 int oracle_dense_attn(const orc_params* p, const void* q, const void* K,
