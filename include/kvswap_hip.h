@@ -194,6 +194,29 @@ kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const v
                                      void* out, void* workspace, size_t workspace_bytes,
                                      void* stream);
 
+/* Sec. 3.4.3 (KV cache manager): the same attention with the KV groups addressed
+ * through a mapping table, as an operating system addresses pages.  K_pool, V_pool
+ * [n_slots, G, d] (kv_dtype) are pools of group-sized slots shared by all problems;
+ * slot_table [B, H_kv, N/G] int32 gives the slot that holds logical group j of
+ * (b, kv head); group idx[m] of a head is read from slot_table[b, g(h), idx[m]].  Slots may
+ * be in any order, need not all be used, and only the selected ones are read.  Slot
+ * numbers are not validated on the device (0 <= slot < n_slots is the caller's duty,
+ * like the contents of idx).  ctx_capacity plays no role here.  The rolling-buffer
+ * arguments are as above (rb_len = 0: none). */
+kvs_status kvs_sparse_decode_attn_paged(const kvs_params* p, const void* q, const void* K_pool,
+                                        const void* V_pool, const int32_t* slot_table,
+                                        int32_t n_slots, const int32_t* idx, const void* rb_K,
+                                        const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                                        void* out, void* workspace, size_t workspace_bytes,
+                                        void* stream);
+
+/* Sec. 3.4.2 (reuse of groups across steps): common[s] = number of group indices that
+ * occur in both idx_prev[s,:] and idx_cur[s,:], per selection set ([B, H_kv], or [B] in
+ * joint mode; int32, device).  Divided by M it is the overlap ratio of two consecutive
+ * steps.  Indices of a row must be unique (any order); out-of-range ones are ignored. */
+kvs_status kvs_selection_overlap(const kvs_params* p, const int32_t* idx_prev,
+                                 const int32_t* idx_cur, int32_t* common, void* stream);
+
 /* One whole decode step of a layer: kvs_predict_select followed by
  * kvs_sparse_decode_attn on the same stream (three launches in all).  idx
  * receives the selection (it is an output here); group_scores may be NULL. */

@@ -21,7 +21,8 @@ EXPORTS = (
     "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata",
     "kvs_build_metadata_rows", "kvs_append_group", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
-    "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_decode_step", "kvs_decode_step_rb",
+    "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_sparse_decode_attn_paged",
+    "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb",
     "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
@@ -121,6 +122,10 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_append_group.restype = ctypes.c_int
     lib.kvs_sparse_decode_attn_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
     lib.kvs_sparse_decode_attn_rb.restype = ctypes.c_int
+    lib.kvs_sparse_decode_attn_paged.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.kvs_sparse_decode_attn_paged.restype = ctypes.c_int
+    lib.kvs_selection_overlap.argtypes = [pp, vp, vp, vp, vp]
+    lib.kvs_selection_overlap.restype = ctypes.c_int
     lib.kvs_decode_step_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.kvs_decode_step_rb.restype = ctypes.c_int
     lib.kvs_predict_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -331,6 +336,39 @@ def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, 
     else:
         st = lib.kvs_sparse_decode_attn_rb(*args, *_rb(p, rb_K, rb_V, rb_len), *tail)
     _check(st, _entry)
+
+
+def kvs_sparse_decode_attn_paged(p: Params, q, K_pool, V_pool, slot_table, idx, out, workspace,
+                                 rb_K=None, rb_V=None, rb_len: int = 0, stream=None) -> None:
+    """K_pool, V_pool [n_slots, G, d]; slot_table [B, H_kv, N/G] int32 (logical group -> slot)."""
+    torch = _torch()
+    kd = _dtype_of(p.kv_dtype)
+    c = p._c()
+    ws, nws = _ws(workspace)
+    if K_pool is None or K_pool.dim() != 3:
+        raise ValueError("K_pool must be [n_slots, G, d]")
+    n_slots = int(K_pool.shape[0])
+    pool_shape = (n_slots, p.group_size, p.head_dim)
+    st = load_library().kvs_sparse_decode_attn_paged(
+        ctypes.byref(c),
+        _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+        _dev(K_pool, kd, pool_shape, "K_pool"), _dev(V_pool, kd, pool_shape, "V_pool"),
+        _dev(slot_table, torch.int32, (p.batch, p.n_kv_heads, p.n_groups), "slot_table"), n_slots,
+        _dev(idx, torch.int32, p.sets + (p.n_select,), "idx"),
+        *_rb(p, rb_K, rb_V, rb_len),
+        _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"), ws, nws, _stream(stream))
+    _check(st, "kvs_sparse_decode_attn_paged")
+
+
+def kvs_selection_overlap(p: Params, idx_prev, idx_cur, common, stream=None) -> None:
+    torch = _torch()
+    c = p._c()
+    st = load_library().kvs_selection_overlap(
+        ctypes.byref(c),
+        _dev(idx_prev, torch.int32, p.sets + (p.n_select,), "idx_prev"),
+        _dev(idx_cur, torch.int32, p.sets + (p.n_select,), "idx_cur"),
+        _dev(common, torch.int32, p.sets, "common"), _stream(stream))
+    _check(st, "kvs_selection_overlap")
 
 
 def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:

@@ -272,25 +272,59 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
   return dev(launch_topk(*p, pl, group_scores, idx, hist, (hipStream_t)stream));
 }
 
-kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const void* K,
-                                     const void* V, const int32_t* idx, const void* rb_K,
-                                     const void* rb_V, int32_t rb_len, int32_t rb_capacity,
-                                     void* out, void* workspace, size_t workspace_bytes,
-                                     void* stream) {
+namespace {
+// shared body of the attention entry points; slot_table == nullptr: K, V are the caches
+kvs_status attend(const kvs_params* p, const void* q, const void* K, const void* V,
+                  const int32_t* slot_table, const int32_t* idx, const void* rb_K,
+                  const void* rb_V, int32_t rb_len, int32_t rb_capacity, void* out,
+                  void* workspace, size_t workspace_bytes, void* stream) {
   if (!p || !q || !K || !V || !idx || !out) return KVS_ERR_NULL;
   kvs_status s = check_params(p, true);
   if (s != KVS_OK) return s;
   RollingBuffer rb;
   if ((s = check_rb(rb_K, rb_V, rb_len, rb_capacity, &rb)) != KVS_OK) return s;
-  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(out))
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(out) ||
+      (slot_table && misaligned(slot_table)))
     return KVS_ERR_ALIGN;
   const Plan pl = make_plan(*p);
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
   float* part_o = (float*)((char*)workspace + pl.off_part_o);
   int* arrivals = (int*)((char*)workspace + pl.off_sync);
-  return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb,
+  return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table,
                          (hipStream_t)stream));
+}
+}  // namespace
+
+kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const void* K,
+                                     const void* V, const int32_t* idx, const void* rb_K,
+                                     const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                                     void* out, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  return attend(p, q, K, V, nullptr, idx, rb_K, rb_V, rb_len, rb_capacity, out, workspace,
+                workspace_bytes, stream);
+}
+
+kvs_status kvs_sparse_decode_attn_paged(const kvs_params* p, const void* q, const void* K_pool,
+                                        const void* V_pool, const int32_t* slot_table,
+                                        int32_t n_slots, const int32_t* idx, const void* rb_K,
+                                        const void* rb_V, int32_t rb_len, int32_t rb_capacity,
+                                        void* out, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+  if (!slot_table) return KVS_ERR_NULL;
+  if (n_slots < 1) return KVS_ERR_SHAPE;
+  return attend(p, q, K_pool, V_pool, slot_table, idx, rb_K, rb_V, rb_len, rb_capacity, out,
+                workspace, workspace_bytes, stream);
+}
+
+kvs_status kvs_selection_overlap(const kvs_params* p, const int32_t* idx_prev,
+                                 const int32_t* idx_cur, int32_t* common, void* stream) {
+  if (!p || !idx_prev || !idx_cur || !common) return KVS_ERR_NULL;
+  const kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(idx_prev) || misaligned(idx_cur) || misaligned(common)) return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  return dev(launch_overlap(*p, pl, idx_prev, idx_cur, common, (hipStream_t)stream));
 }
 
 kvs_status kvs_sparse_decode_attn(const kvs_params* p, const void* q, const void* K, const void* V,

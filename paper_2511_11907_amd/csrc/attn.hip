@@ -29,9 +29,16 @@ constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
 constexpr float kLog2e = 1.4426950408889634f;
 
-// RB: the attended-token list continues into a rolling buffer (compiled out otherwise, so
-// the plain path pays nothing for it).
-template <typename E, int D, int QPK, bool RB>
+// MODE selects what the gather has to support beyond the plain cache; each feature is
+// compiled out of the modes below it, so the plain path pays nothing for them:
+//   kAttnPlain   selected groups are rows of this problem's contiguous cache
+//   kAttnRolling + the attended-token list continues into a rolling buffer (Sec. 3.4.1)
+//   kAttnPaged   + groups are addressed through a mapping table (Sec. 3.4.3): K and V are
+//                  pools of group-sized slots shared by all problems, slot_table[p][j]
+//                  is the slot that holds logical group j of problem p
+constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
+
+template <typename E, int D, int QPK, int MODE>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
@@ -39,7 +46,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int ctx_rows, int M, int log2G,
     int units, int units_per_split, int n_splits, float scale_log2e,
     const typename E::storage* __restrict__ rb_K, const typename E::storage* __restrict__ rb_V,
-    int rb_len, int rb_capacity) {
+    int rb_len, int rb_capacity, const int32_t* __restrict__ slot_table, int n_groups) {
+  constexpr bool RB = MODE >= kAttnRolling;
+  constexpr bool PAGED = MODE == kAttnPaged;
   constexpr int EPL = E::kPerLane;
   constexpr int LPT = D / EPL;       // lanes per token row
   constexpr int TPU = kWave / LPT;   // tokens per unit
@@ -80,8 +89,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     for (int e = 0; e < EPL; ++e) o[h][e] = 0.f;
   }
 
-  const typename E::storage* Kp = K + (size_t)p * ctx_rows * D;
-  const typename E::storage* Vp = V + (size_t)p * ctx_rows * D;
+  const typename E::storage* Kp = PAGED ? K : K + (size_t)p * ctx_rows * D;
+  const typename E::storage* Vp = PAGED ? V : V + (size_t)p * ctx_rows * D;
+  const int32_t* tab = slot_table + (size_t)p * n_groups;  // (only read when PAGED)
   // rolling buffer (Sec. 3.4.1): the newest rb_len tokens follow the selected ones in the
   // token list; they are read from their own small arrays
   const typename E::storage* Kr = rb_K + (size_t)p * rb_capacity * D;
@@ -102,9 +112,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       const int tok = (ub + u) * TPU + ts;  // position in the attended-token list
       ok[u] = (ub + u < u1) && (tok < n_all);
       in_rb[u] = RB && ok[u] && (tok >= n_tok);
-      const int grp = (ok[u] && !in_rb[u]) ? sel[tok >> log2G] : 0;
-      const int row = in_rb[u] ? tok - n_tok : (grp << log2G) + (tok & (G - 1));
-      off[u] = (size_t)(ok[u] ? row : 0) * D + (size_t)c * EPL;
+      const bool in_cache = ok[u] && !in_rb[u];
+      int grp = in_cache ? sel[tok >> log2G] : 0;
+      if constexpr (PAGED) grp = in_cache ? tab[grp] : 0;  // logical group -> slot
+      // (a slot index times G may not fit 32 bits: the pool is shared by all problems)
+      const size_t row = in_rb[u] ? (size_t)(tok - n_tok) : ((size_t)grp << log2G) + (size_t)(tok & (G - 1));
+      off[u] = (ok[u] ? row : 0) * D + (size_t)c * EPL;
     }
     uint4 kv[kAttnUnroll], vv[kAttnUnroll];
 #pragma unroll
@@ -254,7 +267,8 @@ namespace {
 template <typename E, int D, int QPK>
 hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                           const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                          void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
+                          void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                          hipStream_t st) {
   using S = typename E::storage;
   int log2G = 0;
   while ((1 << log2G) < p.group_size) ++log2G;
@@ -266,22 +280,25 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
     hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
                        part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
                        p.n_select, log2G, units, pl.attn_units_per_split, pl.attn_splits,
-                       scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity);
+                       scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity,
+                       slot_table, pl.n_groups);
   };
-  if (rb.len > 0) launch(attn_partial_kernel<E, D, QPK, true>);
-  else launch(attn_partial_kernel<E, D, QPK, false>);
+  if (slot_table) launch(attn_partial_kernel<E, D, QPK, kAttnPaged>);
+  else if (rb.len > 0) launch(attn_partial_kernel<E, D, QPK, kAttnRolling>);
+  else launch(attn_partial_kernel<E, D, QPK, kAttnPlain>);
   return hipGetLastError();
 }
 
 template <typename E, int D>
 hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                       const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                      void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
+                      void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                      hipStream_t st) {
   switch (pl.q_per_kv) {
-    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
-    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
-    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
-    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
   }
   return hipErrorInvalidValue;
 }
@@ -289,10 +306,11 @@ hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const 
 template <typename E>
 hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                     const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                    void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
+                    void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                      hipStream_t st) {
   switch (p.head_dim) {
-    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
-    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+    case 64: return launch_qpk<E, 64>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 128: return launch_qpk<E, 128>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
   }
   return hipErrorInvalidValue;
 }
@@ -301,9 +319,10 @@ hipError_t launch_d(const kvs_params& p, const Plan& pl, const void* q, const vo
 
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st) {
-  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
-  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, st);
+                       void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                      hipStream_t st) {
+  if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+  return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
 }
 
 }  // namespace kvs

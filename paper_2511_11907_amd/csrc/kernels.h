@@ -76,7 +76,13 @@ hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int
                        int* hist, hipStream_t st);
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
-                       void* out, int* arrivals, const RollingBuffer& rb, hipStream_t st);
+                       void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                       hipStream_t st);
+// slot_table != nullptr: K and V are pools [n_slots, G, d] and slot_table [P, NG] maps the
+// logical groups of each problem to slots (Sec. 3.4.3).
+// common[s] = |idx_prev[s,:] ∩ idx_cur[s,:]| per selection set
+hipError_t launch_overlap(const kvs_params& p, const Plan& pl, const int32_t* idx_prev,
+                          const int32_t* idx_cur, int32_t* common, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 }  // namespace kvs

@@ -39,4 +39,45 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Overlap of two selections of one set (Sec. 3.4.2: how many of this step's groups were
+// already selected in the previous step).  The previous selection is marked in a bitmap
+// of N/G bits in LDS, then every current index is looked up; indices of a row are unique,
+// in any order.
+constexpr int kOverlapThreads = 256;
+
+__global__ __launch_bounds__(kOverlapThreads) void overlap_kernel(const int32_t* __restrict__ idx_prev,
+                                                                  const int32_t* __restrict__ idx_cur,
+                                                                  int32_t* __restrict__ common, int M,
+                                                                  int n_groups) {
+  __shared__ uint32_t s_bits[kTopkThreads * kTopkMaxPerLane / 32];  // one bit per group
+  __shared__ int s_count;
+  const int tid = threadIdx.x, set = blockIdx.x;
+  const int words = (n_groups + 31) / 32;
+  for (int i = tid; i < words; i += kOverlapThreads) s_bits[i] = 0u;
+  if (tid == 0) s_count = 0;
+  lds_barrier();
+  const int32_t* a = idx_prev + (size_t)set * M;
+  const int32_t* b = idx_cur + (size_t)set * M;
+  for (int i = tid; i < M; i += kOverlapThreads) {
+    const int g = a[i];
+    if (g >= 0 && g < n_groups) atomicOr(&s_bits[g >> 5], 1u << (g & 31));
+  }
+  lds_barrier();
+  int mine = 0;
+  for (int i = tid; i < M; i += kOverlapThreads) {
+    const int g = b[i];
+    if (g >= 0 && g < n_groups) mine += (s_bits[g >> 5] >> (g & 31)) & 1u;
+  }
+  if (mine) atomicAdd(&s_count, mine);
+  lds_barrier();
+  if (tid == 0) common[set] = s_count;
+}
+
+hipError_t launch_overlap(const kvs_params& p, const Plan& pl, const int32_t* idx_prev,
+                          const int32_t* idx_cur, int32_t* common, hipStream_t st) {
+  hipLaunchKernelGGL(overlap_kernel, dim3(pl.sets), dim3(kOverlapThreads), 0, st, idx_prev, idx_cur,
+                     common, p.n_select, pl.n_groups);
+  return hipGetLastError();
+}
+
 }  // namespace kvs

@@ -175,6 +175,23 @@ def test_rolling_buffer_capacity_and_append_arguments_are_checked_on_the_host():
     assert r(ctypes.byref(c), null, fake, fake, 0, 4, null) == E_NULL
 
 
+def test_mapping_table_and_overlap_arguments_are_checked_on_the_host():
+    lib = kv.load_library()
+    fake, odd, null = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x10004), ctypes.c_void_p(0)
+    big = 1 << 30
+    c = _p()._c()
+    a = lib.kvs_sparse_decode_attn_paged
+    args = lambda tab, n: (ctypes.byref(c), fake, fake, fake, tab, n, fake, null, null, 0, 0, fake, fake, big, null)
+    assert a(*args(null, 100)) == E_NULL
+    assert a(*args(fake, 0)) == E_SHAPE
+    assert a(*args(odd, 100)) == E_ALIGN
+    assert a(ctypes.byref(c), fake, fake, fake, fake, 100, fake, null, null, 0, 0, fake, fake, 64, null) == E_WS
+    o = lib.kvs_selection_overlap
+    assert o(ctypes.byref(c), fake, null, fake, null) == E_NULL
+    assert o(ctypes.byref(c), fake, fake, odd, null) == E_ALIGN
+    assert o(ctypes.byref(_p(n_select=0)._c()), fake, fake, fake, null) == E_SHAPE
+
+
 def test_binding_refuses_host_tensors():
     torch = pytest.importorskip("torch")
     p = _p(ctx_len=64, n_select=2)
