@@ -242,6 +242,26 @@ def time_kernels(wl: Workload, reps: int) -> dict:
     return out
 
 
+def time_build_metadata(wl: Workload, reps: int = 5) -> dict:
+    """The metadata build (outside the step latency): reads all of K once, writes K_lr."""
+    torch, kv, p = wl.torch, wl.kv, wl.p
+    s = wl.slots[0]
+    scratch = torch.empty_like(s["K_lr"])
+    kv.kvs_build_metadata(p, s["K"], s["A"], scratch)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        sl = wl.slots[i % len(wl.slots)]
+        kv.kvs_build_metadata(p, sl["K"], sl["A"], scratch)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = s["K"].numel() * s["K"].element_size() + scratch.numel() * scratch.element_size()
+    return {"us": us, "algorithmic_bytes": nbytes, "gbps": nbytes / us / 1e3,
+            "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS}
+
+
 def load_traffic(cfg_name: str, kernel: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled
     by a plain copy of known size), if a summary for this workload has been committed."""
@@ -296,6 +316,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
     layers = wl.layers_per_step
     us_layer = ms_step * 1e3 / layers
     kern = time_kernels(wl, max(steps, 50))
+    meta_build = time_build_metadata(wl)
     # warm-cache figure for reference: the same step repeated on one copy
     one = Workload.__new__(Workload)
     one.__dict__.update(wl.__dict__)
@@ -321,6 +342,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
         "algorithmic_bytes": ab,
         "copies": len(wl.slots),
         "warm_ms_per_step": warm_ms,
+        "build_metadata": meta_build,
         "layer_ahead": {"us_per_layer": ahead_ms * 1e3 / layers,
                         "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
@@ -382,7 +404,7 @@ def main() -> int:
         st = max(20, min(args.steps, 60))
         r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta)
         others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
-                                          "roofline", "copies", "layer_ahead")}
+                                          "roofline", "copies", "layer_ahead", "build_metadata")}
         others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
 
     line = {
@@ -409,6 +431,7 @@ def main() -> int:
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
         "warm_ms_per_step": main_res["warm_ms_per_step"],
         "layer_ahead": main_res["layer_ahead"],
+        "build_metadata": main_res["build_metadata"],
         "kernel_us": main_res["kernel_us"],
         "algorithmic_bytes": main_res["algorithmic_bytes"],
         "roofline": main_res["roofline"],

@@ -6,6 +6,11 @@
 // the k-th block of d rows of the single adapter: the same tile loop, run over the
 // KV heads with the accumulators kept.
 //
+// Two kernels.  build_metadata_mfma_kernel (bf16 keys, per-head adapters: the shapes the
+// method is run at) puts the contraction on the matrix cores and is bound by reading K;
+// build_metadata_kernel (fp32 keys, and the joint-head loop over KV heads) is the plain
+// fp32 FMA version described next.
+//
 // A workgroup owns a tile of 64 consecutive token rows of one (sequence, KV head)
 // problem (of one sequence in joint-head mode).  The K tile is brought in with coalesced 16-byte loads and parked in
 // LDS as fp32 (row stride d+1 words, so the 64 lanes of a wave, one row each, hit
@@ -78,6 +83,152 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
   }
 }
 
+// ---- matrix-core version ------------------------------------------------------------------
+// K_lr^T (r x tokens) = A^T (r x d) . K^T (d x tokens), 16x16x32 bf16 MFMA tiles with fp32
+// accumulation.  The keys are bf16 already.  The fp32 adapter is split into three bf16
+// terms (hi + mid + lo reproduces all 24 mantissa bits), so every product is exact and the
+// only rounding left is the fp32 accumulation, as in the FMA version.
+//
+// Operand layout of the instruction (checked on the device): lane l supplies row/column
+// (l % 16) and the eight contraction indices (l / 16) * 8 .. + 7 of a 32-wide step, and
+// receives output column (l % 16), rows (l / 16) * 4 .. + 3.  With tokens as the columns,
+// the four lanes that share a token read 64 contiguous bytes of its key row per step
+// (a 32x32 tile would leave 32: measured to be bound by the cache's tag rate at 3 TB/s),
+// and a lane ends up with four consecutive rank indices of one token, i.e. one 8-byte
+// store (bf16) into the row-major K_lr.  The adapter operands are laid out once per
+// workgroup in LDS; each is read once per tile and used for both token blocks of the wave.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+constexpr int kMfmaThreads = 256;
+constexpr int kMfmaWaves = kMfmaThreads / kWave;
+constexpr int kMfmaTokenBlocks = 2;                         // blocks of 16 tokens per wave
+constexpr int kMfmaRowsPerWave = 16 * kMfmaTokenBlocks;
+constexpr int kMfmaRowsPerTile = kMfmaWaves * kMfmaRowsPerWave;
+
+template <typename EM, int D, int MB>  // MB blocks of 16 rank columns (r <= 16 * MB)
+__global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
+    const uint16_t* __restrict__ K, const float* __restrict__ A,
+    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int ctx_rows, int first_row,
+    int row_end, int r, int col0, int cols, float meta_scale) {
+  // this launch produces rank columns col0 .. col0 + cols - 1 (cols <= 16 * MB) of the r
+  constexpr int KS = D / 32;  // contraction steps
+  constexpr int TB = kMfmaTokenBlocks;
+  __shared__ uint4 s_a[3][MB][KS][kWave];  // [split term][rank block][step][lane]
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int p = blockIdx.y, k_head = p % n_kv_heads;
+  const int nl = lane & 15, kq = lane >> 4;
+
+  // adapter operands: entry (mb, ks, lane) holds A[k = ks*32 + kq*8 + j][m = mb*16 + nl],
+  // j = 0..7, as the hi / mid / lo bf16 terms
+  {
+    const float* Ak = A + (size_t)k_head * D * r;
+    for (int e = tid; e < MB * KS * kWave; e += kMfmaThreads) {
+      const int l = e % kWave, ks = (e / kWave) % KS, mb = e / (kWave * KS);
+      const int m = mb * 16 + (l & 15), k0 = ks * 32 + (l >> 4) * 8;
+      uint16_t t[3][8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float x = (m < cols) ? Ak[(size_t)(k0 + j) * r + col0 + m] : 0.f;
+        const uint16_t hi = float_to_bf16_bits(x);
+        const float r1 = x - bf16_bits_to_float(hi);   // exact
+        const uint16_t mid = float_to_bf16_bits(r1);
+        const float r2 = r1 - bf16_bits_to_float(mid);  // exact
+        t[0][j] = hi, t[1][j] = mid, t[2][j] = float_to_bf16_bits(r2);
+      }
+#pragma unroll
+      for (int sp = 0; sp < 3; ++sp)
+        s_a[sp][mb][ks][l] = make_uint4(t[sp][0] | (uint32_t)t[sp][1] << 16, t[sp][2] | (uint32_t)t[sp][3] << 16,
+                                        t[sp][4] | (uint32_t)t[sp][5] << 16, t[sp][6] | (uint32_t)t[sp][7] << 16);
+    }
+  }
+  lds_barrier();
+
+  const uint16_t* Kp = K + (size_t)p * ctx_rows * D + (size_t)kq * 8;
+  typename EM::storage* Op = K_lr + (size_t)p * ctx_rows * r;
+  const int n_tiles = (row_end - first_row + kMfmaRowsPerTile - 1) / kMfmaRowsPerTile;
+
+  auto row_of = [&](int tile, int tb) {
+    return first_row + tile * kMfmaRowsPerTile + wave * kMfmaRowsPerWave + tb * 16 + nl;
+  };
+  auto fetch = [&](int tile, uint4 (&kr)[TB][KS]) {
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int row = min(row_of(tile, tb), row_end - 1);  // rows past the end are computed and dropped
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        kr[tb][ks] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * D + ks * 32);
+    }
+  };
+
+  uint4 kcur[TB][KS], knext[TB][KS];
+  int tile = blockIdx.x;
+  if (tile < n_tiles) fetch(tile, kcur);
+  for (; tile < n_tiles; tile += gridDim.x) {
+    const int tn = tile + gridDim.x;
+    if (tn < n_tiles) fetch(tn, knext);  // next tile's keys travel while this one is multiplied
+
+    // The adapter operands are read from LDS again for every tile: kept in registers across
+    // tiles (what the compiler does if it may) they cost 192 registers and leave one wave
+    // per SIMD.
+    asm volatile("" ::: "memory");
+    f32x4_t acc[TB][MB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) acc[tb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#ifndef KVS_META_TERMS
+#define KVS_META_TERMS 3  // (timing experiments only: fewer terms give wrong low-order bits)
+#endif
+#pragma unroll
+    for (int sp = 0; sp < KVS_META_TERMS; ++sp)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, s_a[sp][mb][ks][lane]);
+#pragma unroll
+          for (int tb = 0; tb < TB; ++tb)
+            acc[tb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                a, __builtin_bit_cast(bf16x8_t, kcur[tb][ks]), acc[tb][mb], 0, 0, 0);
+        }
+
+    // accumulator i of rank block mb is rank index mb*16 + kq*4 + i of this lane's token
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int row = row_of(tile, tb);
+      if (row < row_end) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int m0 = mb * 16 + kq * 4;
+          if (m0 < cols) {  // (a multiple of 16, so a quad is inside or outside as a whole)
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = acc[tb][mb][j] / meta_scale;
+            typename EM::storage* o = Op + (size_t)row * r + col0 + m0;
+            if constexpr (EM::kBytes == 2) {
+              *reinterpret_cast<uint2*>(o) =
+                  make_uint2(float_to_bf16_bits(v[0]) | (uint32_t)float_to_bf16_bits(v[1]) << 16,
+                             float_to_bf16_bits(v[2]) | (uint32_t)float_to_bf16_bits(v[3]) << 16);
+            } else if constexpr (EM::kBytes == 1) {
+              *reinterpret_cast<uint32_t*>(o) = float_to_fp8_e4m3(v[0]) | (uint32_t)float_to_fp8_e4m3(v[1]) << 8 |
+                                                (uint32_t)float_to_fp8_e4m3(v[2]) << 16 |
+                                                (uint32_t)float_to_fp8_e4m3(v[3]) << 24;
+            } else {
+              *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kcur[tb][ks] = knext[tb][ks];
+  }
+}
+
 namespace {
 
 template <typename EK, typename EM, int RC>
@@ -110,11 +261,42 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
                                  const float* A, void* K_lr, int first_row, int n_rows,
                                  hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;
-  const bool kb = p.kv_dtype == KVS_BF16, mb = p.meta_dtype == KVS_BF16;
+  const bool kb = p.kv_dtype == KVS_BF16, mbf = p.meta_dtype == KVS_BF16;
+  if (kb && pl.kv_heads_per_set == 1) {  // matrix-core path (r = 128: two passes of 64 columns)
+    const int tiles = (n_rows + kMfmaRowsPerTile - 1) / kMfmaRowsPerTile;
+    int wgs = (kMetaMfmaTargetWgs + pl.sets - 1) / pl.sets;   // enough workgroups to fill the chip,
+    wgs = wgs < 1 ? 1 : (wgs > tiles ? tiles : wgs);          // each walking several tiles
+    dim3 grid(wgs, pl.sets), block(kMfmaThreads);
+    const float scale = p.meta_scale != 0.f ? p.meta_scale : 1.0f;
+    auto go = [&](auto kernel, auto* out) {
+      for (int col0 = 0; col0 < p.rank; col0 += 64) {
+        const int cols = p.rank - col0 < 64 ? p.rank - col0 : 64;
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, (const uint16_t*)K, A, out, p.n_kv_heads,
+                           pl.ctx_rows, first_row, first_row + n_rows, p.rank, col0, cols, scale);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
+    };
+    const int mb = p.rank >= 64 ? 4 : p.rank / 16;  // 1, 2 or 4 rank blocks per pass
+    const bool d128 = p.head_dim == 128;
+#define KVS_MFMA_CASE(EM, T)                                                                          \
+  if (d128) return mb == 4 ? go(build_metadata_mfma_kernel<EM, 128, 4>, (T*)K_lr)                    \
+                 : mb == 2 ? go(build_metadata_mfma_kernel<EM, 128, 2>, (T*)K_lr)                    \
+                           : go(build_metadata_mfma_kernel<EM, 128, 1>, (T*)K_lr);                   \
+  return mb == 4 ? go(build_metadata_mfma_kernel<EM, 64, 4>, (T*)K_lr)                               \
+       : mb == 2 ? go(build_metadata_mfma_kernel<EM, 64, 2>, (T*)K_lr)                               \
+                 : go(build_metadata_mfma_kernel<EM, 64, 1>, (T*)K_lr);
+    if (p.meta_dtype == KVS_FP8_E4M3) { KVS_MFMA_CASE(FP8Elem, uint8_t) }
+    if (mbf) { KVS_MFMA_CASE(BF16Elem, uint16_t) }
+    KVS_MFMA_CASE(F32Elem, float)
+#undef KVS_MFMA_CASE
+  }
   if (p.meta_dtype == KVS_FP8_E4M3) {
     if (kb) return launch_r<BF16Elem, FP8Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
     return launch_r<F32Elem, FP8Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
   }
+  const bool mb = mbf;
   if (kb && mb) return launch_r<BF16Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
   if (kb && !mb) return launch_r<BF16Elem, F32Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
   if (!kb && mb) return launch_r<F32Elem, BF16Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);

@@ -17,6 +17,7 @@ constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs i
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
+constexpr int kMetaMfmaTargetWgs = 1024;         // workgroups of the matrix-core metadata kernel
 constexpr int kJointMaxFlatDim = 4096;          // H_kv * d the query projection kernel stages in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
