@@ -305,7 +305,8 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0, meta: str = None) -> dict:
                       f"({frac:.3g} of a full layer-step); value scaled to all {cfg.layers} layer(s)"}
 
 
-def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, meta=None) -> dict:
+def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, meta=None,
+            layer_ahead=False) -> dict:
     ab = algorithmic_bytes(cfg, 1 if meta == "fp8" else None)
     if copies is None:
         copies = max(2, int(-(-3 * CACHE_BYTES // ab["step"])))   # rotation >= 3x the caches
@@ -325,7 +326,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
     # the same steps issued layer-ahead (prediction of later layers overlapping the
     # selection and attention of earlier ones); with a one-layer workload the rotating
     # copies stand in for the successive layers of a model
-    ahead_ms = time_steps(wl, steps, warmup, mode, layer_ahead=True) / steps * 1e3
+    ahead_ms = time_steps(wl, steps, warmup, mode, layer_ahead=True) / steps * 1e3 if layer_ahead else None
     dom = max(("predict", "attn"), key=lambda k: kern[k])
     achieved = ab[dom] / (kern[dom] * 1e-6) / 1e9
     res = {
@@ -343,8 +344,9 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
         "copies": len(wl.slots),
         "warm_ms_per_step": warm_ms,
         "build_metadata": meta_build,
-        "layer_ahead": {"us_per_layer": ahead_ms * 1e3 / layers,
-                        "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "layer_ahead": None if ahead_ms is None else {
+            "us_per_layer": ahead_ms * 1e3 / layers,
+            "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if want_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, wl.host0, meta=meta)
@@ -367,6 +369,9 @@ def main() -> int:
     ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
     ap.add_argument("--meta", default="same", choices=["same", "fp8"],
                     help="dtype of the compressed K cache: that of the workload, or 8-bit E4M3")
+    ap.add_argument("--layer-ahead", action="store_true",
+                    help="also time the steps issued layer-ahead (three streams); off by default so that a "
+                         "kernel trace of the default run holds no overlapped launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one 256 MiB device copy (calibration kernel for rocprofv3 --pmc byte counters)")
@@ -397,12 +402,13 @@ def main() -> int:
     cfg = PRESETS[args.config]
     meta = None if args.meta == "same" else args.meta
     main_res = measure(cfg, args.steps, args.warmup, args.mode, args.copies, log,
-                       want_cpu=not args.no_cpu_baseline, meta=meta)
+                       want_cpu=not args.no_cpu_baseline, meta=meta, layer_ahead=args.layer_ahead)
     others = {}
     for name in [x for x in args.extra.split(",") if x and x != args.config]:
         c = PRESETS[name]
         st = max(20, min(args.steps, 60))
-        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta)
+        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta,
+                    layer_ahead=args.layer_ahead)
         others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
                                           "roofline", "copies", "layer_ahead", "build_metadata")}
         others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
