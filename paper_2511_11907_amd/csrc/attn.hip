@@ -22,9 +22,9 @@
 
 namespace kvs {
 
-constexpr int kAttnThreads = 256;
+constexpr int kAttnThreads = kAttnWgThreads;
 constexpr int kAttnWaves = kAttnThreads / kWave;
-constexpr int kAttnUnroll = 4;       // units (K load + V load each) in flight per wave
+constexpr int kAttnUnroll = kAttnUnitsPerWgStep / kAttnWaves;  // units (K load + V load each) in flight per wave
 constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
 constexpr float kLog2e = 1.4426950408889634f;

@@ -13,7 +13,13 @@ namespace kvs {
 constexpr int kPredictWgThreads = 512;
 constexpr int kPredictUnitsPerWgStep = 8 * 8;  // 8 waves x 8 loads in flight
 constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per CU, all resident
-constexpr int kAttnUnitsPerWgStep = 4 * 4;     // 4 waves x 4 (K,V) load pairs in flight
+// (512-lane attention workgroups: in one run, same 512-workgroup grid, 256 -> 512 lanes took
+// c4 from 64.8 to 58.6 us and c2 from 16.1 to 13.5 us, c3 unchanged)
+#ifndef KVS_ATTN_THREADS
+#define KVS_ATTN_THREADS 512
+#endif
+constexpr int kAttnWgThreads = KVS_ATTN_THREADS;
+constexpr int kAttnUnitsPerWgStep = (kAttnWgThreads / 64) * 4;  // waves x 4 (K,V) load pairs in flight
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
