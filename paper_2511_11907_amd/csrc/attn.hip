@@ -39,7 +39,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
 
 template <typename E, int D, int QPK, int MODE>
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
+__global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
     float* part_ml, float* part_o, typename E::storage* __restrict__ out,
@@ -104,19 +104,38 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   // buffer are taken by the last split
   const int u1 = (split == n_splits - 1) ? units : min(units, u0 + units_per_split);
 
+  // Where the selected groups of a batch are (their indices, and through the mapping table
+  // their slots) is looked up one batch ahead, while the previous batch's keys and values
+  // are still on their way: a batch then costs one memory latency, not two in a row.
+  auto locate = [&](int ubase, int (&g)[kAttnUnroll]) {
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      const int tok = (ubase + u) * TPU + ts;  // position in the attended-token list
+      const bool in_cache = (ubase + u < u1) && (tok < n_tok);
+      g[u] = in_cache ? sel[tok >> log2G] : 0;
+    }
+    if constexpr (PAGED) {
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) {
+        const int tok = (ubase + u) * TPU + ts;
+        const bool in_cache = (ubase + u < u1) && (tok < n_tok);
+        g[u] = in_cache ? tab[g[u]] : 0;  // logical group -> slot
+      }
+    }
+  };
+  int grp[kAttnUnroll], grp_next[kAttnUnroll];
+  locate(u0 + wave * kAttnUnroll, grp);
+
   for (int ub = u0 + wave * kAttnUnroll; ub < u1; ub += kAttnWaves * kAttnUnroll) {
     bool ok[kAttnUnroll], in_rb[kAttnUnroll];
     size_t off[kAttnUnroll];
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) {
-      const int tok = (ub + u) * TPU + ts;  // position in the attended-token list
+      const int tok = (ub + u) * TPU + ts;
       ok[u] = (ub + u < u1) && (tok < n_all);
       in_rb[u] = RB && ok[u] && (tok >= n_tok);
-      const bool in_cache = ok[u] && !in_rb[u];
-      int grp = in_cache ? sel[tok >> log2G] : 0;
-      if constexpr (PAGED) grp = in_cache ? tab[grp] : 0;  // logical group -> slot
       // (a slot index times G may not fit 32 bits: the pool is shared by all problems)
-      const size_t row = in_rb[u] ? (size_t)(tok - n_tok) : ((size_t)grp << log2G) + (size_t)(tok & (G - 1));
+      const size_t row = in_rb[u] ? (size_t)(tok - n_tok) : ((size_t)grp[u] << log2G) + (size_t)(tok & (G - 1));
       off[u] = (ok[u] ? row : 0) * D + (size_t)c * EPL;
     }
     uint4 kv[kAttnUnroll], vv[kAttnUnroll];
@@ -126,6 +145,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u)
       vv[u] = *reinterpret_cast<const uint4*>((RB && in_rb[u] ? Vr : Vp) + off[u]);
+    locate(ub + kAttnWaves * kAttnUnroll, grp_next);  // (past the end: nothing is read)
 
     // logits (already in log2 units) of this slot's token against each head
     float z[kAttnUnroll][QPK];
@@ -169,6 +189,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 #pragma unroll
         for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pw[u][h], vf[e], o[h][e]);
     }
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) grp[u] = grp_next[u];
   }
 
   // ---- merge the token slots of the wave (lanes with equal column c) ------------
