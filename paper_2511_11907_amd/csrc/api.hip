@@ -67,7 +67,9 @@ Plan make_plan(const kvs_params& p) {
     const int most = ceil_div(pl.attn_units, kAttnUnitsPerWgStep);
     int splits = want < 1 ? 1 : (want > most ? most : want);
     if (splits > kAttnMaxSplitsPerProblem) splits = kAttnMaxSplitsPerProblem;
-    pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWgStep);
+    // (rounded to one wave's batch only: rounding to a whole workgroup step would make e.g.
+    // 7 splits of 128 units out of 820 where 8 of 104 fill the chip evenly)
+    pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWave);
     pl.attn_splits = ceil_div(pl.attn_units, pl.attn_units_per_split);
   }
 

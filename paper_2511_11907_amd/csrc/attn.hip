@@ -20,6 +20,21 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+// Phase timestamps for the debugging harness (compiled only with -DKVS_ATTN_TRACE_BUILD):
+// one row of 8 wall-clock stamps per workgroup.
+#ifdef KVS_ATTN_TRACE_BUILD
+__device__ long long g_attn_trace[1 << 16];
+#define KVS_ATTN_TRACE(i)                                                                           \
+  do {                                                                                               \
+    if (threadIdx.x == 0) g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)) & 0xFFFF] = wall_clock64(); \
+  } while (0)
+extern "C" int kvs_debug_attn_trace(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), sizeof(long long) * (size_t)n);
+}
+#else
+#define KVS_ATTN_TRACE(i)
+#endif
+
 namespace kvs {
 
 constexpr int kAttnThreads = kAttnWgThreads;
@@ -62,6 +77,12 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int split = blockIdx.x, p = blockIdx.y;
+  KVS_ATTN_TRACE(0);
+#ifdef KVS_ATTN_TRACE_BUILD
+  if (threadIdx.x == 0)  // where the workgroup runs: XCC id (hwreg 20), HW id (hwreg 4)
+    g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + 7) & 0xFFFF] =
+        ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
   const int b = p / n_kv_heads, k = p % n_kv_heads;
   const int n_q_heads = n_kv_heads * QPK;
   const int c = lane % LPT;   // 16-byte column of the row
@@ -125,6 +146,7 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
   };
   int grp[kAttnUnroll], grp_next[kAttnUnroll];
   locate(u0 + wave * kAttnUnroll, grp);
+  KVS_ATTN_TRACE(1);
 
   for (int ub = u0 + wave * kAttnUnroll; ub < u1; ub += kAttnWaves * kAttnUnroll) {
     bool ok[kAttnUnroll], in_rb[kAttnUnroll];
@@ -193,6 +215,7 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
     for (int u = 0; u < kAttnUnroll; ++u) grp[u] = grp_next[u];
   }
 
+  KVS_ATTN_TRACE(2);
   // ---- merge the token slots of the wave (lanes with equal column c) ------------
 #pragma unroll
   for (int h = 0; h < QPK; ++h) {
@@ -243,13 +266,16 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
   __shared__ int s_last;
   __shared__ float s_cw[QPK][kAttnMaxSplits];  // weight of each split, per head
   __shared__ float s_cl[QPK];                  // merged softmax denominators
+  KVS_ATTN_TRACE(3);
   publish_complete_and_barrier();  // the partials are out before the arrival is announced
+  KVS_ATTN_TRACE(4);
   if (tid == 0) {
     const int old = atomicAdd(&arrivals[p], 1);
     s_last = (old == n_splits - 1);
     if (s_last) arrivals[p] = 0;  // leave the counter ready for the next call
   }
   lds_barrier();
+  KVS_ATTN_TRACE(5);
   if (!s_last) return;
   const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
   for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
@@ -282,6 +308,7 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
     if constexpr (E::kBytes == 2) op[i] = float_to_bf16_bits(r);
     else op[i] = r;
   }
+  KVS_ATTN_TRACE(6);
 }
 
 namespace {
