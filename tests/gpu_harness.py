@@ -267,9 +267,9 @@ def compare_metadata(klr_gpu: np.ndarray, klr_ref: np.ndarray, klr_exact: np.nda
     """GPU K_lr (fp32 accumulation over d terms, one rounding) against the oracle's exact
     fp64 products: every element must lie within half a unit in the last place of the
     storage dtype plus the fp32 accumulation bound d * 2^-24 * sum_i |K_i A_ij|.  For bf16
-    storage the result must also be bit-identical to the oracle's rounding except where the
-    exact value sits that close to a rounding boundary (a fraction of a per cent).
-    Returns the fraction of elements that differ from the oracle's rounded array."""
+    and fp8 storage the result must also be bit-identical to the oracle's rounding except
+    where the exact value sits that close to a rounding boundary (a fraction of a per cent
+    of the well-conditioned elements).  Returns that fraction."""
     g = meta_values(klr_gpu)
     r = meta_values(klr_ref)
     if dtype == "fp8":     # saturating format: compare against the clamped exact value
@@ -278,7 +278,12 @@ def compare_metadata(klr_gpu: np.ndarray, klr_ref: np.ndarray, klr_exact: np.nda
     ulp = np.maximum(_ulp(g, dtype), _ulp(klr_exact, dtype))
     assert np.all(np.abs(g - klr_exact) <= 0.5 * ulp + acc + 1e-300), \
         "GPU metadata is further from the exact product than rounding + fp32 accumulation allow"
-    frac = float((g != r).mean())
+    # Bit-identity with the oracle's rounding is asked only of well-conditioned elements:
+    # where the products cancel to far below their magnitudes (an adapter column orthogonal
+    # to every key of a short context) the fp32 accumulation error exceeds the spacing of
+    # the narrow dtype at the tiny result, and only the bound above can hold.
+    well = np.abs(klr_exact) > 1024.0 * acc
+    frac = float((g != r)[well].mean()) if well.any() else 0.0
     if dtype in ("bf16", "fp8"):
         assert frac <= 2e-3, f"too many metadata elements differ from the oracle: {frac}"
     return frac
