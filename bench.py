@@ -289,20 +289,30 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0, meta: str = None) -> dict:
                       head_mode=oracle.HEADS_JOINT if cfg.joint else oracle.HEADS_SEPARATE)
     K, V, q = (np.ascontiguousarray(x[:nb]) for x in (L.K, L.V, L.q))
     klr = oracle.build_metadata(oracle.Shape(**{**sh.__dict__, "n_threads": 8}), K, L.A)  # untimed set-up
-    reps, spent = 0, 0.0
-    while spent < budget_s and reps < 50:
-        t0 = time.perf_counter()
-        r = oracle.predict_select(sh, q, klr, L.A)
-        oracle.sparse_attn(sh, q, K, V, r["idx"])
-        spent += time.perf_counter() - t0
-        reps += 1
+
+    def timed(shape, budget):
+        reps, spent = 0, 0.0
+        while spent < budget and reps < 50:
+            t0 = time.perf_counter()
+            r = oracle.predict_select(shape, q, klr, L.A)
+            oracle.sparse_attn(shape, q, K, V, r["idx"])
+            spent += time.perf_counter() - t0
+            reps += 1
+        return reps, spent
+
+    reps, spent = timed(sh, budget_s)
     tokens = reps * nb                      # sequences advanced by one token
     frac = nb * cfg.n_kv_heads / P          # share of one layer-step that was timed
+    # the same sample with the oracle's own threading over the independent problems
+    threads = max(1, min(16, os.cpu_count() or 1, nb * cfg.n_kv_heads))
+    reps_t, spent_t = timed(oracle.Shape(**{**sh.__dict__, "n_threads": threads}), budget_s / 3)
     return {"value": tokens / spent / cfg.layers, "unit": "tokens/s", "cores": 1, "kind": "oracle",
             "sample": f"{reps} x (predict_select + sparse_attn) of {nb} of {cfg.batch} sequences, "
                       f"{cfg.n_kv_heads} kv heads, one layer, fp64 single thread; "
                       f"{spent / reps * 1e3:.1f} ms per sampled layer-step "
-                      f"({frac:.3g} of a full layer-step); value scaled to all {cfg.layers} layer(s)"}
+                      f"({frac:.3g} of a full layer-step); value scaled to all {cfg.layers} layer(s)",
+            "threaded": {"value": reps_t * nb / spent_t / cfg.layers, "cores": threads,
+                         "ms_per_sampled_layer_step": spent_t / reps_t * 1e3}}
 
 
 def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, meta=None,
