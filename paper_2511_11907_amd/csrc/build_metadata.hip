@@ -6,10 +6,9 @@
 // the k-th block of d rows of the single adapter: the same tile loop, run over the
 // KV heads with the accumulators kept.
 //
-// Two kernels.  build_metadata_mfma_kernel (bf16 keys, per-head adapters: the shapes the
-// method is run at) puts the contraction on the matrix cores and is bound by reading K;
-// build_metadata_kernel (fp32 keys, and the joint-head loop over KV heads) is the plain
-// fp32 FMA version described next.
+// build_metadata_mfma_kernel / build_metadata_mfma_joint_kernel (bf16 keys: the shapes the
+// method is run at) put the contraction on the matrix cores and are bound by reading K;
+// build_metadata_kernel (fp32 keys) is the plain fp32 FMA version described next.
 //
 // A workgroup owns a tile of 64 consecutive token rows of one (sequence, KV head)
 // problem (of one sequence in joint-head mode).  The K tile is brought in with coalesced 16-byte loads and parked in
@@ -229,6 +228,117 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
   }
 }
 
+// ---- matrix-core version, joint-head mode ---------------------------------------------------
+// K_lr[b,n,:] = sum_k K[b,k,n,:] . A_k: the same tiles, with the accumulators of a wave's
+// tokens kept while the KV heads go by.  The adapter block of one head at a time lives in
+// LDS (all H_kv blocks would not fit), so a workgroup restages it per head and amortises
+// that over the 256 token rows it owns per pass; the keys of the head are requested first
+// and travel while the block is staged.
+constexpr int kMfmaJointTokenBlocks = 4;  // blocks of 16 tokens per wave
+constexpr int kMfmaJointRowsPerWave = 16 * kMfmaJointTokenBlocks;
+constexpr int kMfmaJointRowsPerTile = kMfmaWaves * kMfmaJointRowsPerWave;
+
+template <typename EM, int D, int MB>
+__global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_joint_kernel(
+    const uint16_t* __restrict__ K, const float* __restrict__ A,
+    typename EM::storage* __restrict__ K_lr, int n_kv_heads, int ctx_rows, int first_row,
+    int row_end, int r, int col0, int cols, float meta_scale) {
+  constexpr int KS = D / 32;
+  constexpr int TB = kMfmaJointTokenBlocks;
+  __shared__ uint4 s_a[3][MB][KS][kWave];
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int b = blockIdx.y;
+  const int nl = lane & 15, kq = lane >> 4;
+  typename EM::storage* Op = K_lr + (size_t)b * ctx_rows * r;
+  const int n_tiles = (row_end - first_row + kMfmaJointRowsPerTile - 1) / kMfmaJointRowsPerTile;
+
+  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int row0 = first_row + tile * kMfmaJointRowsPerTile + wave * kMfmaJointRowsPerWave + nl;
+    f32x4_t acc[TB][MB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) acc[tb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kh = 0; kh < n_kv_heads; ++kh) {
+      // this head's keys of the wave's tokens: requested before the adapter block is staged
+      const uint16_t* Kp = K + ((size_t)b * n_kv_heads + kh) * ctx_rows * D + (size_t)kq * 8;
+      uint4 kr[TB][KS];
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) {
+        const int row = min(row0 + tb * 16, row_end - 1);  // rows past the end are computed and dropped
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          kr[tb][ks] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * D + ks * 32);
+      }
+      lds_barrier();  // everyone is done with the previous head's block
+      {
+        const float* Ak = A + (size_t)kh * D * r;
+        for (int e = tid; e < MB * KS * kWave; e += kMfmaThreads) {
+          const int l = e % kWave, ks = (e / kWave) % KS, mb = e / (kWave * KS);
+          const int m = mb * 16 + (l & 15), k0 = ks * 32 + (l >> 4) * 8;
+          uint16_t t[3][8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float x = (m < cols) ? Ak[(size_t)(k0 + j) * r + col0 + m] : 0.f;
+            const uint16_t hi = float_to_bf16_bits(x);
+            const float r1 = x - bf16_bits_to_float(hi);   // exact
+            const uint16_t mid = float_to_bf16_bits(r1);
+            const float r2 = r1 - bf16_bits_to_float(mid);  // exact
+            t[0][j] = hi, t[1][j] = mid, t[2][j] = float_to_bf16_bits(r2);
+          }
+#pragma unroll
+          for (int sp = 0; sp < 3; ++sp)
+            s_a[sp][mb][ks][l] = make_uint4(t[sp][0] | (uint32_t)t[sp][1] << 16, t[sp][2] | (uint32_t)t[sp][3] << 16,
+                                            t[sp][4] | (uint32_t)t[sp][5] << 16, t[sp][6] | (uint32_t)t[sp][7] << 16);
+        }
+      }
+      lds_barrier();
+#pragma unroll
+      for (int sp = 0; sp < 3; ++sp)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, s_a[sp][mb][ks][lane]);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+              acc[tb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  a, __builtin_bit_cast(bf16x8_t, kr[tb][ks]), acc[tb][mb], 0, 0, 0);
+          }
+    }
+
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int row = row0 + tb * 16;
+      if (row < row_end) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int m0 = mb * 16 + kq * 4;
+          if (m0 < cols) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = acc[tb][mb][j] / meta_scale;
+            typename EM::storage* o = Op + (size_t)row * r + col0 + m0;
+            if constexpr (EM::kBytes == 2) {
+              *reinterpret_cast<uint2*>(o) =
+                  make_uint2(float_to_bf16_bits(v[0]) | (uint32_t)float_to_bf16_bits(v[1]) << 16,
+                             float_to_bf16_bits(v[2]) | (uint32_t)float_to_bf16_bits(v[3]) << 16);
+            } else if constexpr (EM::kBytes == 1) {
+              *reinterpret_cast<uint32_t*>(o) = float_to_fp8_e4m3(v[0]) | (uint32_t)float_to_fp8_e4m3(v[1]) << 8 |
+                                                (uint32_t)float_to_fp8_e4m3(v[2]) << 16 |
+                                                (uint32_t)float_to_fp8_e4m3(v[3]) << 24;
+            } else {
+              *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 namespace {
 
 template <typename EK, typename EM, int RC>
@@ -262,8 +372,10 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
                                  hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;
   const bool kb = p.kv_dtype == KVS_BF16, mbf = p.meta_dtype == KVS_BF16;
-  if (kb && pl.kv_heads_per_set == 1) {  // matrix-core path (r = 128: two passes of 64 columns)
-    const int tiles = (n_rows + kMfmaRowsPerTile - 1) / kMfmaRowsPerTile;
+  if (kb) {  // matrix-core paths (r = 128: two passes of 64 columns)
+    const bool joint = pl.kv_heads_per_set > 1;
+    const int rows_per_tile = joint ? kMfmaJointRowsPerTile : kMfmaRowsPerTile;
+    const int tiles = (n_rows + rows_per_tile - 1) / rows_per_tile;
     int wgs = (kMetaMfmaTargetWgs + pl.sets - 1) / pl.sets;   // enough workgroups to fill the chip,
     wgs = wgs < 1 ? 1 : (wgs > tiles ? tiles : wgs);          // each walking several tiles
     dim3 grid(wgs, pl.sets), block(kMfmaThreads);
@@ -280,17 +392,21 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
     };
     const int mb = p.rank >= 64 ? 4 : p.rank / 16;  // 1, 2 or 4 rank blocks per pass
     const bool d128 = p.head_dim == 128;
+#define KVS_MFMA_PICK(KERNEL, EM, T)                                                                  \
+  if (d128) return mb == 4 ? go(KERNEL<EM, 128, 4>, (T*)K_lr)                                        \
+                 : mb == 2 ? go(KERNEL<EM, 128, 2>, (T*)K_lr)                                        \
+                           : go(KERNEL<EM, 128, 1>, (T*)K_lr);                                       \
+  return mb == 4 ? go(KERNEL<EM, 64, 4>, (T*)K_lr)                                                   \
+       : mb == 2 ? go(KERNEL<EM, 64, 2>, (T*)K_lr)                                                   \
+                 : go(KERNEL<EM, 64, 1>, (T*)K_lr);
 #define KVS_MFMA_CASE(EM, T)                                                                          \
-  if (d128) return mb == 4 ? go(build_metadata_mfma_kernel<EM, 128, 4>, (T*)K_lr)                    \
-                 : mb == 2 ? go(build_metadata_mfma_kernel<EM, 128, 2>, (T*)K_lr)                    \
-                           : go(build_metadata_mfma_kernel<EM, 128, 1>, (T*)K_lr);                   \
-  return mb == 4 ? go(build_metadata_mfma_kernel<EM, 64, 4>, (T*)K_lr)                               \
-       : mb == 2 ? go(build_metadata_mfma_kernel<EM, 64, 2>, (T*)K_lr)                               \
-                 : go(build_metadata_mfma_kernel<EM, 64, 1>, (T*)K_lr);
+  if (joint) { KVS_MFMA_PICK(build_metadata_mfma_joint_kernel, EM, T) }                              \
+  KVS_MFMA_PICK(build_metadata_mfma_kernel, EM, T)
     if (p.meta_dtype == KVS_FP8_E4M3) { KVS_MFMA_CASE(FP8Elem, uint8_t) }
     if (mbf) { KVS_MFMA_CASE(BF16Elem, uint16_t) }
     KVS_MFMA_CASE(F32Elem, float)
 #undef KVS_MFMA_CASE
+#undef KVS_MFMA_PICK
   }
   if (p.meta_dtype == KVS_FP8_E4M3) {
     if (kb) return launch_r<BF16Elem, FP8Elem>(p, pl, K, A, K_lr, first_row, n_rows, st);
