@@ -292,7 +292,7 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0, meta: str = None) -> dict:
 
     def timed(shape, budget):
         reps, spent = 0, 0.0
-        while spent < budget and reps < 50:
+        while spent < budget and reps < 2000:
             t0 = time.perf_counter()
             r = oracle.predict_select(shape, q, klr, L.A)
             oracle.sparse_attn(shape, q, K, V, r["idx"])
