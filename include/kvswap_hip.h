@@ -60,9 +60,11 @@
  * allocating (or zero-fill the buffer yourself); every call then leaves the
  * counters zero for the next one.
  * The rest of the workspace is undefined on entry and on return.  Calls that
- * share a workspace must be ordered on one stream (they would race otherwise),
- * and a workspace prepared for one kvs_params serves any params that need no
- * more bytes.
+ * share a workspace must be ordered on one stream (they would race otherwise).
+ * The layout of the counter area depends only on batch, n_kv_heads and head_mode:
+ * a buffer that is large enough stays valid while those are unchanged (e.g. through
+ * a decode loop whose ctx_len grows: size it for the largest ctx_len); when they
+ * change, call kvs_workspace_init again with the new params first.
  *
  * Errors: every function validates its arguments on the host before anything is
  * launched and returns a kvs_status; nothing is thrown or aborted across the
