@@ -90,15 +90,24 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
   const int G = 1 << log2G;
   const int n_tok = M << log2G;
 
-  // queries of the QPK heads of this KV head, pre-multiplied by scale*log2(e)
-  float qr[QPK][EPL];
+  // Queries of the QPK heads of this KV head.  fp32: as floats, pre-multiplied by
+  // scale*log2(e).  bf16: left packed as they are stored (half the registers) and multiplied
+  // against the packed keys with the two-element bf16 dot instruction, which forms the
+  // products exactly in fp32; the scale is applied to the finished logit.
+  constexpr bool kPackedQK = (E::kBytes == 2);
+  float qr[kPackedQK ? 1 : QPK][kPackedQK ? 1 : EPL];
+  uint4 qp[kPackedQK ? QPK : 1];
 #pragma unroll
   for (int h = 0; h < QPK; ++h) {
     const size_t off = ((size_t)b * n_q_heads + (size_t)k * QPK + h) * D + (size_t)c * EPL;
     const uint4 v = *reinterpret_cast<const uint4*>(q + off);
-    unpack16<E>(v, qr[h]);
+    if constexpr (kPackedQK) {
+      qp[h] = v;
+    } else {
+      unpack16<E>(v, qr[h]);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qr[h][e] *= scale_log2e;
+      for (int e = 0; e < EPL; ++e) qr[h][e] *= scale_log2e;
+    }
   }
 
   float m[QPK], l[QPK], o[QPK][EPL];
@@ -173,14 +182,25 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
     float z[kAttnUnroll][QPK];
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) {
-      float kf[EPL];
-      unpack16<E>(kv[u], kf);
+      if constexpr (kPackedQK) {
 #pragma unroll
-      for (int h = 0; h < QPK; ++h) {
-        float acc = 0.f;
+        for (int h = 0; h < QPK; ++h) {
+          float acc = dot2_bf16(qp[h].x, kv[u].x, 0.f);
+          acc = dot2_bf16(qp[h].y, kv[u].y, acc);
+          acc = dot2_bf16(qp[h].z, kv[u].z, acc);
+          acc = dot2_bf16(qp[h].w, kv[u].w, acc);
+          z[u][h] = allreduce_lanes<OpSum, 1, LPT>(acc) * scale_log2e;
+        }
+      } else {
+        float kf[EPL];
+        unpack16<E>(kv[u], kf);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(qr[h][e], kf[e], acc);
-        z[u][h] = allreduce_lanes<OpSum, 1, LPT>(acc);
+        for (int h = 0; h < QPK; ++h) {
+          float acc = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc = fmaf(qr[h][e], kf[e], acc);
+          z[u][h] = allreduce_lanes<OpSum, 1, LPT>(acc);
+        }
       }
     }
     // online softmax update, one rescale per batch

@@ -85,6 +85,12 @@ __device__ __forceinline__ uint8_t float_to_fp8_e4m3(float x) {
   return (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(c, c, 0, false) & 0xFF);
 }
 
+// a.lo*b.lo + a.hi*b.hi + c over two packed bf16 pairs, products and sum in fp32.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
 // Scalar load of one stored element as fp32 (runtime dtype; cold paths only).
 __device__ __forceinline__ float load_as_float(const void* base, int is_bf16, size_t i) {
   return is_bf16 ? bf16_bits_to_float(((const uint16_t*)base)[i]) : ((const float*)base)[i];

@@ -19,7 +19,7 @@ constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per C
 #define KVS_ATTN_THREADS 512
 #endif
 constexpr int kAttnWgThreads = KVS_ATTN_THREADS;
-constexpr int kAttnUnitsPerWave = 4;                             // (K,V) load pairs a wave keeps in flight
+constexpr int kAttnUnitsPerWave = 4;  // (K,V) load pairs a wave keeps in flight (5: no gain, 6: spills)
 constexpr int kAttnUnitsPerWgStep = (kAttnWgThreads / 64) * kAttnUnitsPerWave;
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
