@@ -44,7 +44,7 @@ Plan make_plan(const kvs_params& p) {
   pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
 
   // predict: one resident wave of workgroups over the whole chip, each streaming at
-  // least one full step of its 16 waves
+  // least one full step of its eight waves
   const int meta_epl = p.meta_dtype == KVS_FP8_E4M3 ? 16 : (p.meta_dtype == KVS_BF16 ? 8 : 4);
   pl.meta_lanes_per_row = p.rank / meta_epl;
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;

@@ -5,7 +5,7 @@
 // Split-K flash-decode.  A (sequence, KV head) problem owns M groups = M*G tokens;
 // the token list is cut into "units" of one wave-wide 16-byte-per-lane load
 // (64/LPT tokens, LPT lanes per token), units are dealt to `attn_splits`
-// workgroups, and inside a workgroup to its four waves.  All H_q/H_kv query heads
+// workgroups, and inside a workgroup to its waves.  All H_q/H_kv query heads
 // that share the KV head are processed together so K and V are read once (GQA
 // head packing).  A lane keeps, for its 16-byte column of the head dimension, an
 // independent online-softmax state (running max, running sum, weighted V sum) per
