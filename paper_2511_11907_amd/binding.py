@@ -222,22 +222,25 @@ def kvs_workspace_init(p: Params, workspace, stream=None) -> None:
            "kvs_workspace_init")
 
 
-def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:
-    kvs_build_metadata_rows(p, K, A, K_lr, 0, p.ctx_len, stream, _what="kvs_build_metadata")
-
-
-def kvs_build_metadata_rows(p: Params, K, A, K_lr, first_row: int, n_rows: int, stream=None,
-                            _what="kvs_build_metadata_rows") -> None:
+def _metadata_args(p: Params, K, A, K_lr):
     torch = _torch()
     kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
+    return (_dev(K, kd, (p.batch, p.n_kv_heads, p.rows, p.head_dim), "K"),
+            _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
+            _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"))
+
+
+def kvs_build_metadata(p: Params, K, A, K_lr, stream=None) -> None:
     c = p._c()
-    st = load_library().kvs_build_metadata_rows(
-        ctypes.byref(c),
-        _dev(K, kd, (p.batch, p.n_kv_heads, p.rows, p.head_dim), "K"),
-        _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
-        _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
-        int(first_row), int(n_rows), _stream(stream))
-    _check(st, _what)
+    st = load_library().kvs_build_metadata(ctypes.byref(c), *_metadata_args(p, K, A, K_lr), _stream(stream))
+    _check(st, "kvs_build_metadata")
+
+
+def kvs_build_metadata_rows(p: Params, K, A, K_lr, first_row: int, n_rows: int, stream=None) -> None:
+    c = p._c()
+    st = load_library().kvs_build_metadata_rows(ctypes.byref(c), *_metadata_args(p, K, A, K_lr),
+                                                int(first_row), int(n_rows), _stream(stream))
+    _check(st, "kvs_build_metadata_rows")
 
 
 def _rb(p: Params, rb_K, rb_V, rb_len: int):
@@ -313,29 +316,30 @@ def kvs_select_topk(p: Params, group_scores, idx, workspace=None, stream=None) -
     _check(st, "kvs_select_topk")
 
 
-def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None) -> None:
-    kvs_sparse_decode_attn_rb(p, q, K, V, idx, None, None, 0, out, workspace, stream,
-                              _entry="kvs_sparse_decode_attn")
-
-
-def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, workspace, stream=None,
-                              _entry="kvs_sparse_decode_attn_rb") -> None:
+def _attn_args(p: Params, q, K, V, idx, out, workspace, stream):
+    """(head, tail) argument lists shared by the attention entry points."""
     torch = _torch()
     kd = _dtype_of(p.kv_dtype)
-    c = p._c()
     ws, nws = _ws(workspace)
     kv_shape = (p.batch, p.n_kv_heads, p.rows, p.head_dim)
-    args = [ctypes.byref(c),
-            _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+    head = [_dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
             _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V"),
             _dev(idx, torch.int32, p.sets + (p.n_select,), "idx")]
     tail = [_dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"), ws, nws, _stream(stream)]
-    lib = load_library()
-    if _entry == "kvs_sparse_decode_attn":
-        st = lib.kvs_sparse_decode_attn(*args, *tail)
-    else:
-        st = lib.kvs_sparse_decode_attn_rb(*args, *_rb(p, rb_K, rb_V, rb_len), *tail)
-    _check(st, _entry)
+    return head, tail
+
+
+def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None) -> None:
+    c = p._c()
+    head, tail = _attn_args(p, q, K, V, idx, out, workspace, stream)
+    _check(load_library().kvs_sparse_decode_attn(ctypes.byref(c), *head, *tail), "kvs_sparse_decode_attn")
+
+
+def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, workspace, stream=None) -> None:
+    c = p._c()
+    head, tail = _attn_args(p, q, K, V, idx, out, workspace, stream)
+    _check(load_library().kvs_sparse_decode_attn_rb(ctypes.byref(c), *head, *_rb(p, rb_K, rb_V, rb_len), *tail),
+           "kvs_sparse_decode_attn_rb")
 
 
 def kvs_sparse_decode_attn_paged(p: Params, q, K_pool, V_pool, slot_table, idx, out, workspace,
@@ -371,30 +375,32 @@ def kvs_selection_overlap(p: Params, idx_prev, idx_cur, common, stream=None) -> 
     _check(st, "kvs_selection_overlap")
 
 
-def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:
-    kvs_decode_step_rb(p, q, K_lr, A, K, V, None, None, 0, idx, group_scores, out, workspace, stream,
-                       _entry="kvs_decode_step")
-
-
-def kvs_decode_step_rb(p: Params, q, K_lr, A, K, V, rb_K, rb_V, rb_len, idx, group_scores, out,
-                       workspace, stream=None, _entry="kvs_decode_step_rb") -> None:
+def _step_args(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream):
+    """(head, tail) argument lists shared by the whole-step entry points."""
     torch = _torch()
     kd, md = _dtype_of(p.kv_dtype), _dtype_of(p.meta_dtype)
-    c = p._c()
     ws, nws = _ws(workspace)
     kv_shape = (p.batch, p.n_kv_heads, p.rows, p.head_dim)
     gs = ctypes.c_void_p(0) if group_scores is None else _dev(
         group_scores, torch.float32, p.sets + (p.n_groups,), "group_scores")
-    head = [ctypes.byref(c),
-            _dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
+    head = [_dev(q, kd, (p.batch, p.n_q_heads, p.head_dim), "q"),
             _dev(K_lr, md, p.sets + (p.rows, p.rank), "K_lr"),
             _dev(A, torch.float32, (p.n_kv_heads, p.head_dim, p.rank), "A"),
             _dev(K, kd, kv_shape, "K"), _dev(V, kd, kv_shape, "V")]
     tail = [_dev(idx, torch.int32, p.sets + (p.n_select,), "idx"), gs,
             _dev(out, kd, (p.batch, p.n_q_heads, p.head_dim), "out"), ws, nws, _stream(stream)]
-    lib = load_library()
-    if _entry == "kvs_decode_step":
-        st = lib.kvs_decode_step(*head, *tail)
-    else:
-        st = lib.kvs_decode_step_rb(*head, *_rb(p, rb_K, rb_V, rb_len), *tail)
-    _check(st, _entry)
+    return head, tail
+
+
+def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:
+    c = p._c()
+    head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream)
+    _check(load_library().kvs_decode_step(ctypes.byref(c), *head, *tail), "kvs_decode_step")
+
+
+def kvs_decode_step_rb(p: Params, q, K_lr, A, K, V, rb_K, rb_V, rb_len, idx, group_scores, out,
+                       workspace, stream=None) -> None:
+    c = p._c()
+    head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream)
+    _check(load_library().kvs_decode_step_rb(ctypes.byref(c), *head, *_rb(p, rb_K, rb_V, rb_len), *tail),
+           "kvs_decode_step_rb")
