@@ -66,6 +66,10 @@
  * a decode loop whose ctx_len grows: size it for the largest ctx_len); when they
  * change, call kvs_workspace_init again with the new params first.
  *
+ * Values: inputs are expected to be finite.  Infinities or NaNs in q, K, V, A or K_lr
+ * are not detected; they give unspecified selections and outputs (never an access
+ * outside the buffers).
+ *
  * Errors: every function validates its arguments on the host before anything is
  * launched and returns a kvs_status; nothing is thrown or aborted across the
  * ABI.  Contents of idx are NOT validated on the device: out-of-range indices
