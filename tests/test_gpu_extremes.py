@@ -103,3 +103,40 @@ def test_step_replayed_from_a_graph_matches_eager_every_time(mode):
     flat = lambda a: a.reshape((-1,) + a.shape[len(p.sets):])
     for i, (ig, gr, bd) in enumerate(zip(flat(want[0][0].cpu().numpy()), flat(ref["gs"]), flat(ref["boundary"]))):
         H.check_index_margin(ig, gr, bd, f"graph set {i}")
+
+
+def test_non_finite_metadata_still_gives_a_well_formed_selection():
+    """Infinities and NaNs are outside the contract, but whatever comes out must still be M
+    distinct in-range group indices in ascending order (all index arithmetic is integer
+    work on the scores' bit patterns), and nothing may be written outside the outputs."""
+    cfg = PRESETS["c2"].replace(name="nonfinite", batch=2, ctx_len=4096, n_select=103)
+    L = make_layer(cfg)
+    p, sh = H.kv_params(cfg), H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    g = np.random.default_rng(0)
+    flat = klr.reshape(-1)
+    where = g.choice(flat.size, 600, replace=False)
+    flat[where[:200]] = 0x7F80      # +inf (bf16 bits)
+    flat[where[200:400]] = 0xFF80   # -inf
+    flat[where[400:]] = 0x7FC0      # NaN
+    D = H.DeviceLayer(L)
+    ws = H.workspace(p)
+    guard = 64
+    idx = torch.full((cfg.batch * cfg.n_kv_heads * cfg.n_select + 2 * guard,), -7, dtype=torch.int32, device=H.DEV)
+    view = idx[guard:-guard].view(cfg.batch, cfg.n_kv_heads, cfg.n_select)
+    out = torch.zeros((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=D.q.dtype, device=H.DEV)
+    for _ in range(2):      # twice: the counters must come back to zero even then
+        kv.kvs_decode_step(p, D.q, H.to_dev(klr), D.A, D.K, D.V, view, None, out, ws)
+        torch.cuda.synchronize()
+        got = view.cpu().numpy()
+        assert got.min() >= 0 and got.max() < cfg.n_groups
+        assert np.all(np.diff(got, axis=-1) > 0)
+        assert torch.all(idx[:guard] == -7) and torch.all(idx[-guard:] == -7)
+    # and the workspace still serves a clean problem afterwards
+    klr_ok = oracle.build_metadata(sh, L.K, L.A)
+    kv.kvs_decode_step(p, D.q, H.to_dev(klr_ok), D.A, D.K, D.V, view, None, out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.predict_select(sh, L.q, klr_ok, L.A)
+    for i, (ig, gr, bd) in enumerate(zip(view.cpu().numpy().reshape(-1, cfg.n_select),
+                                         ref["gs"].reshape(-1, cfg.n_groups), ref["boundary"].reshape(-1, 2))):
+        H.check_index_margin(ig, gr, bd, f"after non-finite, set {i}")
