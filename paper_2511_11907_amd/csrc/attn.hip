@@ -153,31 +153,32 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
       }
     }
   };
-  int grp[kAttnUnroll], grp_next[kAttnUnroll];
-  locate(u0 + wave * kAttnUnroll, grp);
-  KVS_ATTN_TRACE(1);
-
-  for (int ub = u0 + wave * kAttnUnroll; ub < u1; ub += kAttnWaves * kAttnUnroll) {
-    bool ok[kAttnUnroll], in_rb[kAttnUnroll];
+  // request(ub, g, kv, vv): issue the K and V loads of the batch that starts at unit ub, whose
+  // groups (slots) g were looked up before.  Units past the end load row 0 and are ignored.
+  auto request = [&](int ub, const int (&g)[kAttnUnroll], uint4 (&kv)[kAttnUnroll], uint4 (&vv)[kAttnUnroll]) {
     size_t off[kAttnUnroll];
+    bool rbf[kAttnUnroll];
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) {
       const int tok = (ub + u) * TPU + ts;
-      ok[u] = (ub + u < u1) && (tok < n_all);
-      in_rb[u] = RB && ok[u] && (tok >= n_tok);
+      const bool ok = (ub + u < u1) && (tok < n_all);
+      rbf[u] = RB && ok && (tok >= n_tok);
       // (a slot index times G may not fit 32 bits: the pool is shared by all problems)
-      const size_t row = in_rb[u] ? (size_t)(tok - n_tok) : ((size_t)grp[u] << log2G) + (size_t)(tok & (G - 1));
-      off[u] = (ok[u] ? row : 0) * D + (size_t)c * EPL;
+      const size_t row = rbf[u] ? (size_t)(tok - n_tok) : ((size_t)g[u] << log2G) + (size_t)(tok & (G - 1));
+      off[u] = (ok ? row : 0) * D + (size_t)c * EPL;
     }
-    uint4 kv[kAttnUnroll], vv[kAttnUnroll];
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u)
-      kv[u] = *reinterpret_cast<const uint4*>((RB && in_rb[u] ? Kr : Kp) + off[u]);
+      kv[u] = *reinterpret_cast<const uint4*>((RB && rbf[u] ? Kr : Kp) + off[u]);
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u)
-      vv[u] = *reinterpret_cast<const uint4*>((RB && in_rb[u] ? Vr : Vp) + off[u]);
-    locate(ub + kAttnWaves * kAttnUnroll, grp_next);  // (past the end: nothing is read)
-
+      vv[u] = *reinterpret_cast<const uint4*>((RB && rbf[u] ? Vr : Vp) + off[u]);
+  };
+  // consume(ub, kv, vv): online-softmax update with the batch that starts at unit ub
+  auto consume = [&](int ub, const uint4 (&kv)[kAttnUnroll], const uint4 (&vv)[kAttnUnroll]) {
+    bool ok[kAttnUnroll];
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) ok[u] = (ub + u < u1) && ((ub + u) * TPU + ts < n_all);
     // logits (already in log2 units) of this slot's token against each head
     float z[kAttnUnroll][QPK];
 #pragma unroll
@@ -231,6 +232,18 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
 #pragma unroll
         for (int e = 0; e < EPL; ++e) o[h][e] = fmaf(pw[u][h], vf[e], o[h][e]);
     }
+  };
+
+  constexpr int kStep = kAttnWaves * kAttnUnroll;
+  const int ub0 = u0 + wave * kAttnUnroll;
+  int grp[kAttnUnroll], grp_next[kAttnUnroll];
+  uint4 kv[kAttnUnroll], vv[kAttnUnroll];
+  locate(ub0, grp);
+  KVS_ATTN_TRACE(1);
+  for (int ub = ub0; ub < u1; ub += kStep) {
+    request(ub, grp, kv, vv);
+    locate(ub + kStep, grp_next);  // (past the end: nothing is read)
+    consume(ub, kv, vv);
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) grp[u] = grp_next[u];
   }
