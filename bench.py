@@ -242,6 +242,23 @@ def time_kernels(wl: Workload, reps: int) -> dict:
     return out
 
 
+def time_step_spread(wl: Workload, steps: int) -> dict:
+    """Spread of the single-step latency: eager steps over the rotating copies with a HIP
+    event between consecutive steps (each interval also holds one event record)."""
+    torch = wl.torch
+    wl.run(min(8, steps))
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        wl.step(i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    us = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 / wl.layers_per_step for i in range(steps))
+    pick = lambda f: us[min(len(us) - 1, int(f * len(us)))]
+    return {"p10": pick(0.10), "median": pick(0.50), "p90": pick(0.90), "steps": steps, "mode": "eager"}
+
+
 def time_build_metadata(wl: Workload, reps: int = 5) -> dict:
     """The metadata build (outside the step latency): reads all of K once, writes K_lr."""
     torch, kv, p = wl.torch, wl.kv, wl.p
@@ -328,6 +345,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
     us_layer = ms_step * 1e3 / layers
     kern = time_kernels(wl, max(steps, 50))
     meta_build = time_build_metadata(wl)
+    spread = time_step_spread(wl, max(steps, 50))
     # warm-cache figure for reference: the same step repeated on one copy
     one = Workload.__new__(Workload)
     one.__dict__.update(wl.__dict__)
@@ -353,6 +371,7 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
         "algorithmic_bytes": ab,
         "copies": len(wl.slots),
         "warm_ms_per_step": warm_ms,
+        "us_per_layer_spread": spread,
         "build_metadata": meta_build,
         "layer_ahead": None if ahead_ms is None else {
             "us_per_layer": ahead_ms * 1e3 / layers,
@@ -383,6 +402,10 @@ def main() -> int:
                     help="also time the steps issued layer-ahead (three streams); off by default so that a "
                          "kernel trace of the default run holds no overlapped launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    # a workload's layer geometry can be changed, e.g. to that of another model of Sec. 4.1
+    # (--q-heads 40 --group-size 12 --ctx-len 32760 --n-select 33: a Qwen3-14B layer at G = 12)
+    for flag in ("batch", "q-heads", "kv-heads", "ctx-len", "rank", "group-size", "n-select"):
+        ap.add_argument("--" + flag, type=int, default=None, help="override this field of the workload")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one 256 MiB device copy (calibration kernel for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -410,6 +433,14 @@ def main() -> int:
         del src, dst
 
     cfg = PRESETS[args.config]
+    over = {field: getattr(args, arg) for arg, field in
+            (("batch", "batch"), ("q_heads", "n_q_heads"), ("kv_heads", "n_kv_heads"), ("ctx_len", "ctx_len"),
+             ("rank", "rank"), ("group_size", "group_size"), ("n_select", "n_select"))
+            if getattr(args, arg) is not None}
+    if over:
+        cfg = cfg.replace(name=cfg.name + "*", **over)
+        if "rank" in over:
+            cfg = cfg.replace(planted_rank=min(cfg.rank, cfg.planted_rank))
     meta = None if args.meta == "same" else args.meta
     main_res = measure(cfg, args.steps, args.warmup, args.mode, args.copies, log,
                        want_cpu=not args.no_cpu_baseline, meta=meta, layer_ahead=args.layer_ahead)
@@ -420,7 +451,8 @@ def main() -> int:
         r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta,
                     layer_ahead=args.layer_ahead)
         others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
-                                          "roofline", "copies", "layer_ahead", "build_metadata")}
+                                          "roofline", "copies", "layer_ahead", "build_metadata",
+                                          "us_per_layer_spread")}
         others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
 
     line = {
@@ -446,6 +478,7 @@ def main() -> int:
         "step_hbm_gbps": main_res["step_gbps"],
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
         "warm_ms_per_step": main_res["warm_ms_per_step"],
+        "us_per_layer_spread": main_res["us_per_layer_spread"],
         "layer_ahead": main_res["layer_ahead"],
         "build_metadata": main_res["build_metadata"],
         "kernel_us": main_res["kernel_us"],

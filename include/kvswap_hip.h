@@ -76,7 +76,10 @@
  * passed to kvs_sparse_decode_attn are a caller error.
  *
  * Supported shapes: d in {64, 128}; r in {16, 32, 64, 128} with r <= d
- * (r <= H_kv*d in joint mode); G in {1, 2, 4, 8, 16}; H_q / H_kv in {1, 2, 4, 8};
+ * (r <= H_kv*d in joint mode); 1 <= G <= 16, any integer (the parameter solver of
+ * App. A.4 searches G upwards from 1, and the appendix's rolling-buffer table uses
+ * G = 12); H_q / H_kv from 1 to 8 (the models of Sec. 4.1 have 3, 4, 5, 7 or 8 query
+ * heads per KV head);
  * N % G == 0; 1 <= M <= N/G; N/G <= 32768; B * H_kv <= 65535; N * d < 2^31;
  * joint mode: H_kv * d <= 4096; ctx_capacity * d < 2^31; rb_len <= 256.
  */

@@ -15,7 +15,6 @@ namespace {
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // Launch-shape targets.  A tuning build (-DKVS_TUNING) lets the environment override
 // them for sweeps; the shipped library uses the constants.
@@ -48,7 +47,9 @@ Plan make_plan(const kvs_params& p) {
   const int meta_epl = p.meta_dtype == KVS_FP8_E4M3 ? 16 : (p.meta_dtype == KVS_BF16 ? 8 : 4);
   pl.meta_lanes_per_row = p.rank / meta_epl;
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;
-  pl.predict_units = ceil_div(p.ctx_len, pl.meta_rows_per_unit);
+  pl.group_slots = 1;  // row slots per group in the prediction pass: G or the next power of two
+  while (pl.group_slots < p.group_size) pl.group_slots *= 2;
+  pl.predict_units = ceil_div(pl.n_groups * pl.group_slots, pl.meta_rows_per_unit);
   {
     const int want = ceil_div(target("KVS_PREDICT_WGS", kPredictTargetWgs), pl.sets);
     const int most = ceil_div(pl.predict_units, kPredictUnitsPerWgStep);
@@ -116,9 +117,9 @@ kvs_status check_params(const kvs_params* p, bool need_select) {
   // supported set
   if (p->head_dim != 64 && p->head_dim != 128) return KVS_ERR_UNSUPPORTED;
   if (p->rank != 16 && p->rank != 32 && p->rank != 64 && p->rank != 128) return KVS_ERR_UNSUPPORTED;
-  if (!is_pow2(p->group_size) || p->group_size > 16) return KVS_ERR_UNSUPPORTED;
+  if (p->group_size > 16) return KVS_ERR_UNSUPPORTED;
   const int qpk = p->n_q_heads / p->n_kv_heads;
-  if (!is_pow2(qpk) || qpk > 8) return KVS_ERR_UNSUPPORTED;
+  if (qpk > 8) return KVS_ERR_UNSUPPORTED;
   if (ng > 32768) return KVS_ERR_UNSUPPORTED;
   // index arithmetic inside the kernels is 32-bit per problem and 64-bit across problems
   const long long rows = p->ctx_capacity > 0 ? p->ctx_capacity : p->ctx_len;

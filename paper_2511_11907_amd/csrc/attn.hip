@@ -54,11 +54,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
 
 template <typename E, int D, int QPK, int MODE>
-__global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_kernel(
+__global__ __launch_bounds__(kAttnThreads, QPK <= 5 ? 4 : 2) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
     float* part_ml, float* part_o, typename E::storage* __restrict__ out,
-    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int ctx_rows, int M, int log2G,
+    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int ctx_rows, int M, int G,
+    int log2G, uint32_t recipG,
     int units, int units_per_split, int n_splits, float scale_log2e,
     const typename E::storage* __restrict__ rb_K, const typename E::storage* __restrict__ rb_V,
     int rb_len, int rb_capacity, const int32_t* __restrict__ slot_table, int n_groups) {
@@ -87,8 +88,13 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
   const int n_q_heads = n_kv_heads * QPK;
   const int c = lane % LPT;   // 16-byte column of the row
   const int ts = lane / LPT;  // token slot within the unit
-  const int G = 1 << log2G;
-  const int n_tok = M << log2G;
+  const int n_tok = M * G;
+  // position of a token of the attended list -> which of the M selected groups it is in.
+  // log2G < 0: G is not a power of two and recipG = floor(2^32 / G) + 1, which makes the
+  // high half of tok * recipG equal to tok / G for every tok below 2^28 / G.
+  auto group_of = [&](int tok) {
+    return log2G >= 0 ? tok >> log2G : (int)__umulhi((uint32_t)tok, recipG);
+  };
 
   // Queries of the QPK heads of this KV head.  fp32: as floats, pre-multiplied by
   // scale*log2(e).  bf16: left packed as they are stored (half the registers) and multiplied
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
     for (int u = 0; u < kAttnUnroll; ++u) {
       const int tok = (ubase + u) * TPU + ts;  // position in the attended-token list
       const bool in_cache = (ubase + u < u1) && (tok < n_tok);
-      g[u] = in_cache ? sel[tok >> log2G] : 0;
+      g[u] = in_cache ? sel[group_of(tok)] : 0;
     }
     if constexpr (PAGED) {
 #pragma unroll
@@ -164,7 +170,8 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 4 ? 4 : 2) void attn_partial_k
       const bool ok = (ub + u < u1) && (tok < n_all);
       rbf[u] = RB && ok && (tok >= n_tok);
       // (a slot index times G may not fit 32 bits: the pool is shared by all problems)
-      const size_t row = rbf[u] ? (size_t)(tok - n_tok) : ((size_t)g[u] << log2G) + (size_t)(tok & (G - 1));
+      const size_t row = rbf[u] ? (size_t)(tok - n_tok)
+                                : (size_t)g[u] * (size_t)G + (size_t)(tok - group_of(tok) * G);
       off[u] = (ok ? row : 0) * D + (size_t)c * EPL;
     }
 #pragma unroll
@@ -352,8 +359,11 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
                           void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
                           hipStream_t st) {
   using S = typename E::storage;
+  const int G = p.group_size;
   int log2G = 0;
-  while ((1 << log2G) < p.group_size) ++log2G;
+  while ((1 << log2G) < G) ++log2G;
+  if ((1 << log2G) != G) log2G = -1;
+  const uint32_t recipG = (uint32_t)((1ull << 32) / (unsigned)G + 1);  // (only read when log2G < 0)
   const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
   // units of the whole attended-token list: the selected tokens, then the rolling buffer
@@ -361,7 +371,7 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
   auto launch = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
                        part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
-                       p.n_select, log2G, units, pl.attn_units_per_split, pl.attn_splits,
+                       p.n_select, G, log2G, recipG, units, pl.attn_units_per_split, pl.attn_splits,
                        scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity,
                        slot_table, pl.n_groups);
   };
@@ -379,7 +389,11 @@ hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const 
   switch (pl.q_per_kv) {
     case 1: return launch_partial<E, D, 1>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
     case 2: return launch_partial<E, D, 2>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 3: return launch_partial<E, D, 3>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
     case 4: return launch_partial<E, D, 4>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 5: return launch_partial<E, D, 5>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 6: return launch_partial<E, D, 6>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
+    case 7: return launch_partial<E, D, 7>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
     case 8: return launch_partial<E, D, 8>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
   }
   return hipErrorInvalidValue;

@@ -49,6 +49,7 @@ struct Plan {
   // predict
   int meta_lanes_per_row;   // lanes of 16 B that cover one K_lr row
   int meta_rows_per_unit;   // rows covered by one wave-wide 1 KiB load
+  int group_slots;          // row slots per group in the prediction pass (G, or the next power of two)
   int predict_units;        // wave-loads per problem
   int predict_units_per_wg;
   int predict_chunks;       // workgroups per problem

@@ -14,6 +14,12 @@
 // in-register all-reduce over those LPR lanes and the group max with a second
 // all-reduce over the lanes (or consecutive units) that hold the group's rows.
 //
+// Group sizes that are not a power of two run on the PAD instantiation of the next power
+// of two G: every group gets G row slots of which the last G - g_real stay empty (no
+// load is useful there, the score counts as -inf for the max and 0 for the mean), so
+// groups still never straddle a unit or a batch.  The bytes moved are the same; the
+// empty slots only cost issue slots.
+//
 // Joint-head mode (Sec. 3.2 design (b)): there is one K_lr per sequence and the score is
 // summed over all query heads, head h projected with the block A_{g(h)} of the single
 // adapter.  The sum still commutes:
@@ -41,12 +47,12 @@ constexpr int kPredictWaves = kPredictThreads / kWave;
 constexpr int kPredictUnroll = kPredictUnitsPerWgStep / kPredictWaves;  // wave-loads in flight per wave
 static_assert(kPredictUnroll * kPredictWaves == kPredictUnitsPerWgStep, "granule mismatch");
 
-template <typename E, int R, int G, bool HIST>
+template <typename E, int R, int G, bool HIST, bool PAD>
 __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     const void* __restrict__ q, int q_is_bf16, const typename E::storage* __restrict__ K_lr,
     const float* __restrict__ A, float* gs, int n_kv_heads, int q_per_kv, int d,
-    int N, int ctx_rows, int units, int units_per_wg, int mean, int* __restrict__ hist,
-    const float* __restrict__ qlr, float meta_scale) {
+    int n_groups, int g_real, int ctx_rows, int units, int units_per_wg, int mean,
+    int* __restrict__ hist, const float* __restrict__ qlr, float meta_scale) {
   constexpr int EPL = E::kPerLane;
   constexpr int LPR = R / EPL;          // lanes per row
   constexpr int RPU = kWave / LPR;      // rows per unit
@@ -73,7 +79,9 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   const int rl = lane / LPR;  // row within the unit
 
   const typename E::storage* Kp = K_lr + (size_t)p * ctx_rows * R;
-  float* gsp = gs + (size_t)p * (N / G);
+  float* gsp = gs + (size_t)p * n_groups;
+  const int N = n_groups * g_real;   // rows of the compressed cache
+  const int n_slots = n_groups * G;  // row slots (== N unless the groups are padded)
   const int u0 = blockIdx.x * units_per_wg;
   const int u1 = min(units, u0 + units_per_wg);
 
@@ -88,9 +96,17 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int unit = unit_of(step_base, u);
-      const int row = unit * RPU + rl;
-      ok[u] = (unit < u1) && (row < N);
-      const size_t off = (size_t)(ok[u] ? row : 0) * R + (size_t)c * EPL;
+      const int slot = unit * RPU + rl;
+      size_t off;
+      if constexpr (PAD) {
+        const int row = (slot / G) * g_real + (slot % G);
+        ok[u] = (unit < u1) && (slot < n_slots) && ((slot % G) < g_real);
+        // (a slot without a row reads a valid row nearby, one its neighbours fetch anyway)
+        off = (size_t)(unit < u1 ? min(row, N - 1) : 0) * R + (size_t)c * EPL;
+      } else {
+        ok[u] = (unit < u1) && (slot < N);
+        off = (size_t)(ok[u] ? slot : 0) * R + (size_t)c * EPL;
+      }
       v[u] = *reinterpret_cast<const uint4*>(Kp + off);
     }
   };
@@ -149,7 +165,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
     lds_barrier();  // the histogram is cleared before anyone counts into it
   }
 
-  const float inv_g = 1.0f / (float)G;
+  const float inv_g = 1.0f / (float)g_real;
+  const float empty = mean ? 0.f : -__builtin_huge_valf();  // score of an empty row slot
 
   while (ub < u1) {
     float sc[U];
@@ -161,6 +178,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc = fmaf(qr[e], f[e], acc);
       sc[u] = allreduce_lanes<OpSum, 1, LPR>(acc);  // token score, on all LPR lanes of the row
+      if constexpr (PAD) sc[u] = ok[u] ? sc[u] : empty;
     }
     // Group representatives go through a per-wave LDS line so that they leave as one
     // coalesced store per batch (scattered 4-byte stores per unit cost ~8 % of the
@@ -190,7 +208,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
       // valid iff its first row is
       const int row0 = unit_of(ub, 0) * RPU;
       const int grp0 = row0 / G;
-      const int row_end = min(N, u1 * RPU);
+      const int row_end = min(n_slots, u1 * RPU);
 #pragma unroll
       for (int t = lane; t < kGroupsPerBatch; t += kWave) {
         if ((grp0 + t) * G < row_end) {
@@ -256,7 +274,7 @@ __global__ __launch_bounds__(kProjectThreads) void project_query_kernel(
 
 namespace {
 
-template <typename E, int R, int G>
+template <typename E, int R, int G, bool PAD>
 hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
                       const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
   dim3 grid(pl.predict_chunks, pl.sets), block(kPredictThreads);
@@ -269,27 +287,34 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const 
     if (e != hipSuccess) return e;
   }
   if (hist)
-    hipLaunchKernelGGL((predict_kernel<E, R, G, true>), grid, block, 0, st, q, q_bf16,
+    hipLaunchKernelGGL((predict_kernel<E, R, G, true, PAD>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
-                       p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean, hist,
-                       (const float*)qlr, scale);
+                       p.head_dim, pl.n_groups, p.group_size, pl.ctx_rows, pl.predict_units,
+                       pl.predict_units_per_wg, mean, hist, (const float*)qlr, scale);
   else
-    hipLaunchKernelGGL((predict_kernel<E, R, G, false>), grid, block, 0, st, q, q_bf16,
+    hipLaunchKernelGGL((predict_kernel<E, R, G, false, PAD>), grid, block, 0, st, q, q_bf16,
                        (const typename E::storage*)K_lr, A, gs, p.n_kv_heads, pl.q_per_kv,
-                       p.head_dim, p.ctx_len, pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean,
-                       (int*)nullptr, (const float*)qlr, scale);
+                       p.head_dim, pl.n_groups, p.group_size, pl.ctx_rows, pl.predict_units,
+                       pl.predict_units_per_wg, mean, (int*)nullptr, (const float*)qlr, scale);
   return hipGetLastError();
 }
 
 template <typename E, int R>
 hipError_t launch_g(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
                     const float* A, float* gs, int* hist, float* qlr, hipStream_t st) {
-  switch (p.group_size) {
-    case 1: return launch_one<E, R, 1>(p, pl, q, K_lr, A, gs, hist, qlr, st);
-    case 2: return launch_one<E, R, 2>(p, pl, q, K_lr, A, gs, hist, qlr, st);
-    case 4: return launch_one<E, R, 4>(p, pl, q, K_lr, A, gs, hist, qlr, st);
-    case 8: return launch_one<E, R, 8>(p, pl, q, K_lr, A, gs, hist, qlr, st);
-    case 16: return launch_one<E, R, 16>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+  const bool pad = pl.group_slots != p.group_size;  // G is not a power of two
+  switch (pl.group_slots) {  // the group size, or the next power of two
+    case 1: return launch_one<E, R, 1, false>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 2: return launch_one<E, R, 2, false>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 4:
+      return pad ? launch_one<E, R, 4, true>(p, pl, q, K_lr, A, gs, hist, qlr, st)
+                 : launch_one<E, R, 4, false>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 8:
+      return pad ? launch_one<E, R, 8, true>(p, pl, q, K_lr, A, gs, hist, qlr, st)
+                 : launch_one<E, R, 8, false>(p, pl, q, K_lr, A, gs, hist, qlr, st);
+    case 16:
+      return pad ? launch_one<E, R, 16, true>(p, pl, q, K_lr, A, gs, hist, qlr, st)
+                 : launch_one<E, R, 16, false>(p, pl, q, K_lr, A, gs, hist, qlr, st);
   }
   return hipErrorInvalidValue;
 }

@@ -61,9 +61,15 @@ def _p(**kw):
     (dict(reduce=2), E_DTYPE),
     (dict(head_dim=96, rank=32), E_UNSUP),
     (dict(rank=48), E_UNSUP),
-    (dict(group_size=3, ctx_len=32769), E_UNSUP),
+    (dict(group_size=3, ctx_len=32769), OK),  # any group size up to 16
+    (dict(group_size=12, ctx_len=32760), OK),
+    (dict(group_size=12), E_SHAPE),           # 32768 is not a multiple of 12
+    (dict(group_size=17, ctx_len=17 * 1900), E_UNSUP),
     (dict(group_size=32), E_UNSUP),
-    (dict(n_q_heads=24), E_UNSUP),            # 3 heads per kv head
+    (dict(n_q_heads=24), OK),                 # 3 heads per kv head (LLaMA3-3B)
+    (dict(n_q_heads=40), OK),                 # 5 (Qwen3-14B)
+    (dict(n_q_heads=56), OK),                 # 7 (Qwen2.5-VL-7B has 28 / 4)
+    (dict(n_q_heads=72), E_UNSUP),            # 9 heads per kv head
     (dict(n_q_heads=128), E_UNSUP),           # 16 heads per kv head
     (dict(group_size=1, ctx_len=65536, n_select=10), E_UNSUP),  # NG > 32768
     (dict(group_size=1, ctx_len=32768, n_select=10), OK),

@@ -49,6 +49,10 @@ CASES = [
     PRESETS["c2j"].replace(name="c2js", batch=2, ctx_len=4096, n_select=103),
     Config("f32_g1_qpk8", 1, 2, 8, 1, 64, 1024, 16, 1, 33, "f32", 16, 0.1, 8),
     Config("bf16_g16_qpk2", 1, 2, 4, 2, 128, 2048, 64, 16, 9, "bf16", 32, 0.1, 8),
+    # slots of 12, 3 and 6 rows; 5, 3 and 7 query heads per KV head
+    Config("bf16_g12_qpk5", 1, 2, 10, 2, 128, 12 * 170, 32, 12, 33, "bf16", 32, 0.1, 8),
+    Config("f32_g3_qpk3", 1, 2, 6, 2, 64, 3 * 683, 16, 3, 41, "f32", 16, 0.1, 8),
+    Config("bf16_g6_qpk7", 1, 1, 7, 1, 128, 6 * 300, 64, 6, 20, "bf16", 32, 0.1, 8),
 ]
 
 

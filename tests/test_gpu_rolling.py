@@ -57,6 +57,11 @@ CASES = [
     (PRESETS["c2j"].replace(name="c2js", batch=2, ctx_len=4096, n_select=103), 4, 4),
     (Config("f32_g1_qpk8", 1, 2, 8, 1, 64, 1024, 16, 1, 33, "f32", 16, 0.1, 8), 3, 5),
     (Config("bf16_g16_qpk2", 1, 2, 4, 2, 128, 2048, 64, 16, 9, "bf16", 32, 0.1, 8), 16, 16),
+    # group sizes and head ratios off the powers of two (App. A.4 searches G in steps of one;
+    # Qwen3-14B has 5 query heads per KV head, LLaMA3-3B 3, Qwen2.5-VL-7B 7)
+    (Config("bf16_g12_qpk5", 1, 2, 10, 2, 128, 12 * 170, 32, 12, 33, "bf16", 32, 0.1, 8), 24, 12),
+    (Config("f32_g3_qpk3", 1, 2, 6, 2, 64, 3 * 683, 16, 3, 41, "f32", 16, 0.1, 8), 5, 3),
+    (Config("bf16_g6_qpk7", 1, 1, 7, 1, 128, 6 * 300, 64, 6, 20, "bf16", 32, 0.1, 8), 0, 7),
 ]
 
 
@@ -105,14 +110,17 @@ def test_attention_with_rolling_buffer_and_spare_capacity(cfg, spare, cap):
     _say(cfg.name, stats)
 
 
+@pytest.mark.parametrize("shape", ["g4_qpk4", "g12_qpk5"])
 @pytest.mark.parametrize("joint", [False, True], ids=["per_head", "joint"])
-def test_decode_loop_appends_groups_and_matches_the_oracle_every_step(joint):
+def test_decode_loop_appends_groups_and_matches_the_oracle_every_step(joint, shape):
     """A decode loop over 3 G + 2 tokens: each new token enters the rolling buffer and is
     attended at once; when the buffer holds a group it is appended to the cache (rows and
     metadata) and takes part in the prediction from then on."""
     base = PRESETS["c2j" if joint else "c2"]
+    if shape == "g12_qpk5":                               # the Qwen3-14B head geometry at G = 12
+        base = base.replace(n_q_heads=40, group_size=12)
     G = base.group_size
-    N0, steps = 2048, 3 * G + 2
+    N0, steps = 2048 // G * G, 3 * G + 2
     cap_rows = N0 + 4 * G
     cfg = base.replace(name="loop", batch=2, ctx_len=cap_rows, n_select=52)
     L = make_layer(cfg)                                   # rows beyond N0 are the tokens to come
@@ -177,4 +185,5 @@ def test_decode_loop_appends_groups_and_matches_the_oracle_every_step(joint):
             drK[:] = float("nan")
             drV[:] = float("nan")
     assert appended == 3 and N == N0 + 3 * G and rb_len == 2
-    _say("decode_loop_" + ("joint" if joint else "per_head"), {"worst_attn_err": worst, "appended": appended})
+    _say(f"decode_loop_{shape}_" + ("joint" if joint else "per_head"),
+         {"worst_attn_err": worst, "appended": appended})
