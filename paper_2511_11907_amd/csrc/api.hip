@@ -64,7 +64,8 @@ Plan make_plan(const kvs_params& p) {
   pl.kv_toks_per_unit = 64 / pl.kv_lanes_per_tok;
   pl.attn_units = ceil_div(p.n_select * p.group_size, pl.kv_toks_per_unit);
   {
-    const int want = ceil_div(target("KVS_ATTN_WGS", kAttnTargetWgs), pl.problems);
+    const int wgs = attn_mfma_applies(p, pl) ? kAttnMfmaTargetWgs : kAttnTargetWgs;
+    const int want = ceil_div(target("KVS_ATTN_WGS", wgs), pl.problems);
     const int most = ceil_div(pl.attn_units, kAttnUnitsPerWgStep);
     int splits = want < 1 ? 1 : (want > most ? most : want);
     if (splits > kAttnMaxSplitsPerProblem) splits = kAttnMaxSplitsPerProblem;

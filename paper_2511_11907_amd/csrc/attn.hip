@@ -31,30 +31,26 @@ __device__ long long g_attn_trace[1 << 16];
 extern "C" int kvs_debug_attn_trace(long long* host, int n) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), sizeof(long long) * (size_t)n);
 }
-#else
-#define KVS_ATTN_TRACE(i)
 #endif
+
+#include "attn_merge.h"
 
 namespace kvs {
 
-constexpr int kAttnThreads = kAttnWgThreads;
-constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kAttnUnroll = kAttnUnitsPerWgStep / kAttnWaves;  // units (K load + V load each) in flight per wave
-constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
-constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
-constexpr float kLog2e = 1.4426950408889634f;
 
-// MODE selects what the gather has to support beyond the plain cache; each feature is
-// compiled out of the modes below it, so the plain path pays nothing for them:
-//   kAttnPlain   selected groups are rows of this problem's contiguous cache
-//   kAttnRolling + the attended-token list continues into a rolling buffer (Sec. 3.4.1)
-//   kAttnPaged   + groups are addressed through a mapping table (Sec. 3.4.3): K and V are
-//                  pools of group-sized slots shared by all problems, slot_table[p][j]
-//                  is the slot that holds logical group j of problem p
-constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
+// Waves per SIMD the register budget is set for: 4 (128 registers, two workgroups per
+// compute unit) wherever that compiles without spills - a spilled register is reloaded in
+// order behind the loads in flight and stalls the wave for a full memory latency.
+template <typename E, int QPK, int MODE>
+constexpr int attn_min_waves() {
+  if (QPK <= 4) return 4;
+  if (QPK == 5 && (E::kBytes == 4 || MODE == kAttnPlain)) return 4;
+  return 2;
+}
 
 template <typename E, int D, int QPK, int MODE>
-__global__ __launch_bounds__(kAttnThreads, QPK <= 5 ? 4 : 2) void attn_partial_kernel(
+__global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) void attn_partial_kernel(
     const typename E::storage* __restrict__ q, const typename E::storage* __restrict__ K,
     const typename E::storage* __restrict__ V, const int32_t* __restrict__ idx,
     float* part_ml, float* part_o, typename E::storage* __restrict__ out,
@@ -71,10 +67,7 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 5 ? 4 : 2) void attn_partial_k
   static_assert(LPT == 8 || LPT == 16 || LPT == 32, "row must span 8, 16 or 32 lanes");
 
   // per-wave partial states, merged by the whole workgroup at the end
-  __shared__ float s_m[kAttnWaves][QPK];
-  __shared__ float s_l[kAttnWaves][QPK];
-  __shared__ float s_w[kAttnWaves][QPK];
-  __shared__ float s_o[kAttnWaves][QPK][D];
+  __shared__ AttnWaveStates<D, QPK> ws;
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int split = blockIdx.x, p = blockIdx.y;
@@ -271,83 +264,16 @@ __global__ __launch_bounds__(kAttnThreads, QPK <= 5 ? 4 : 2) void attn_partial_k
 #pragma unroll
     for (int h = 0; h < QPK; ++h) {
       if (c == 0) {
-        s_m[wave][h] = m[h];
-        s_l[wave][h] = l[h];
+        ws.m[wave][h] = m[h];
+        ws.l[wave][h] = l[h];
       }
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s_o[wave][h][c * EPL + e] = o[h][e];
+      for (int e = 0; e < EPL; ++e) ws.o[wave][h][c * EPL + e] = o[h][e];
     }
   }
-  lds_barrier();
-  // per head: workgroup max, weights, sum of l
-  float* ml = part_ml + ((size_t)p * n_splits + split) * QPK * 2;
-  if (tid < QPK) {
-    float mt = kNegBig;
-    for (int s = 0; s < kAttnWaves; ++s) mt = fmaxf(mt, s_m[s][tid]);
-    float lt = 0.f;
-    for (int s = 0; s < kAttnWaves; ++s) {
-      const float w = __builtin_amdgcn_exp2f(s_m[s][tid] - mt);
-      s_w[s][tid] = w;
-      lt += w * s_l[s][tid];
-    }
-    publish_store(&ml[tid * 2 + 0], mt);
-    publish_store(&ml[tid * 2 + 1], lt);
-  }
-  lds_barrier();
-  float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
-  for (int i = tid; i < QPK * D; i += kAttnThreads) {
-    const int h = i / D, dd = i % D;
-    float acc = 0.f;
-    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][h][dd], acc);
-    publish_store(&po[i], acc);
-  }
-
-  // ---- the last workgroup of the problem merges the splits ------------------------
-  __shared__ int s_last;
-  __shared__ float s_cw[QPK][kAttnMaxSplits];  // weight of each split, per head
-  __shared__ float s_cl[QPK];                  // merged softmax denominators
-  KVS_ATTN_TRACE(3);
-  publish_complete_and_barrier();  // the partials are out before the arrival is announced
-  KVS_ATTN_TRACE(4);
-  if (tid == 0) {
-    const int old = atomicAdd(&arrivals[p], 1);
-    s_last = (old == n_splits - 1);
-    if (s_last) arrivals[p] = 0;  // leave the counter ready for the next call
-  }
-  lds_barrier();
-  KVS_ATTN_TRACE(5);
-  if (!s_last) return;
-  const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
-  for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
-    float mt = kNegBig;
-    for (int s = lane; s < n_splits; s += kWave) mt = fmaxf(mt, load_published(&pml[((size_t)s * QPK + h) * 2]));
-    mt = allreduce_lanes<OpMax, 1, kWave>(mt);
-    float lt = 0.f;
-    for (int s = lane; s < n_splits; s += kWave) {
-      const float w = __builtin_amdgcn_exp2f(load_published(&pml[((size_t)s * QPK + h) * 2]) - mt);
-      s_cw[h][s] = w;
-      lt = fmaf(w, load_published(&pml[((size_t)s * QPK + h) * 2 + 1]), lt);
-    }
-    lt = allreduce_lanes<OpSum, 1, kWave>(lt);
-    if (lane == 0) s_cl[h] = lt;
-  }
-  lds_barrier();
-  const float* ppo = part_o + (size_t)p * n_splits * QPK * D;
-  typename E::storage* op = out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D;
-  for (int i = tid; i < QPK * D; i += kAttnThreads) {
-    const int h = i / D;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 4 <= n_splits; s += 4) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[j] = fmaf(s_cw[h][s + j], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
-    }
-    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[h][s], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
-    const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
-    if constexpr (E::kBytes == 2) op[i] = float_to_bf16_bits(r);
-    else op[i] = r;
-  }
+  attn_merge_and_finish<E, D, QPK>(ws, part_ml, part_o,
+                                   out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D, arrivals, p,
+                                   split, n_splits);
   KVS_ATTN_TRACE(6);
 }
 
@@ -368,10 +294,11 @@ hipError_t launch_partial(const kvs_params& p, const Plan& pl, const void* q, co
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
   // units of the whole attended-token list: the selected tokens, then the rolling buffer
   const int units = (p.n_select * p.group_size + rb.len + pl.kv_toks_per_unit - 1) / pl.kv_toks_per_unit;
+  const int units_per_split = attn_units_per_split_with_buffer(pl, units);
   auto launch = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
                        part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
-                       p.n_select, G, log2G, recipG, units, pl.attn_units_per_split, pl.attn_splits,
+                       p.n_select, G, log2G, recipG, units, units_per_split, pl.attn_splits,
                        scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity,
                        slot_table, pl.n_groups);
   };
@@ -417,6 +344,8 @@ hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
                        void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
                       hipStream_t st) {
+  if (attn_mfma_applies(p, pl))
+    return launch_attn_mfma(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
   if (p.kv_dtype == KVS_BF16) return launch_d<BF16Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
   return launch_d<F32Elem>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table, st);
 }

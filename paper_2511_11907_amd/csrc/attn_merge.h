@@ -1,0 +1,136 @@
+// Second half of the split-K attention kernels, shared by the vector-ALU and the
+// matrix-core variant: merge the per-wave online-softmax states of a workgroup, publish
+// the workgroup's partial result, and let the workgroup of a problem that arrives last
+// merge the splits and write the output (log-sum-exp rescaling throughout; logits are in
+// log2 units).
+#pragma once
+
+#include "device_utils.h"
+#include "kernels.h"
+
+#ifndef KVS_ATTN_TRACE
+#define KVS_ATTN_TRACE(i)  // phase timestamps, only defined by the debugging build
+#endif
+
+namespace kvs {
+
+constexpr int kAttnThreads = kAttnWgThreads;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
+constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
+constexpr float kLog2e = 1.4426950408889634f;
+
+// MODE selects what the gather has to support beyond the plain cache; each feature is
+// compiled out of the modes below it, so the plain path pays nothing for them:
+//   kAttnPlain   selected groups are rows of this problem's contiguous cache
+//   kAttnRolling + the attended-token list continues into a rolling buffer (Sec. 3.4.1)
+//   kAttnPaged   + groups are addressed through a mapping table (Sec. 3.4.3): K and V are
+//                  pools of group-sized slots shared by all problems, slot_table[p][j]
+//                  is the slot that holds logical group j of problem p
+constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
+
+// Units per split when the attended-token list is longer than the selection the plan was
+// made for (the rolling buffer's tokens follow the selected ones): the number of splits -
+// and with it the workspace layout - stays, the units are dealt out evenly again, so the
+// buffer does not cost the last split an extra batch.
+inline int attn_units_per_split_with_buffer(const Plan& pl, int units) {
+  const int even = (units + pl.attn_splits - 1) / pl.attn_splits;
+  const int rounded = (even + kAttnUnitsPerWave - 1) / kAttnUnitsPerWave * kAttnUnitsPerWave;
+  return rounded > pl.attn_units_per_split ? rounded : pl.attn_units_per_split;
+}
+
+// Per-wave states as the first half leaves them in LDS: for wave w and head h the running
+// max m, the sum l of 2^(z - m) and the accordingly weighted sum o of value rows.
+template <int D, int QPK>
+struct AttnWaveStates {
+  float m[kAttnWaves][QPK];
+  float l[kAttnWaves][QPK];
+  float w[kAttnWaves][QPK];  // scratch of the merge
+  float o[kAttnWaves][QPK][D];
+};
+
+// Every lane of the workgroup calls this after its wave's state is written to `ws` (no
+// barrier needed before the call).  p: problem (sequence, KV head); op: the QPK output
+// rows of this problem.
+template <typename E, int D, int QPK>
+__device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws, float* part_ml,
+                                                      float* part_o, typename E::storage* op,
+                                                      int* __restrict__ arrivals, int p, int split,
+                                                      int n_splits) {
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  auto& s_m = ws.m;
+  auto& s_l = ws.l;
+  auto& s_w = ws.w;
+  auto& s_o = ws.o;
+  lds_barrier();
+  // per head: workgroup max, weights, sum of l
+  float* ml = part_ml + ((size_t)p * n_splits + split) * QPK * 2;
+  if (tid < QPK) {
+    float mt = kNegBig;
+    for (int s = 0; s < kAttnWaves; ++s) mt = fmaxf(mt, s_m[s][tid]);
+    float lt = 0.f;
+    for (int s = 0; s < kAttnWaves; ++s) {
+      const float w = __builtin_amdgcn_exp2f(s_m[s][tid] - mt);
+      s_w[s][tid] = w;
+      lt += w * s_l[s][tid];
+    }
+    publish_store(&ml[tid * 2 + 0], mt);
+    publish_store(&ml[tid * 2 + 1], lt);
+  }
+  lds_barrier();
+  float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {
+    const int h = i / D, dd = i % D;
+    float acc = 0.f;
+    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][h][dd], acc);
+    publish_store(&po[i], acc);
+  }
+
+  // ---- the last workgroup of the problem merges the splits ------------------------
+  __shared__ int s_last;
+  __shared__ float s_cw[QPK][kAttnMaxSplits];  // weight of each split, per head
+  __shared__ float s_cl[QPK];                  // merged softmax denominators
+  KVS_ATTN_TRACE(3);
+  publish_complete_and_barrier();  // the partials are out before the arrival is announced
+  KVS_ATTN_TRACE(4);
+  if (tid == 0) {
+    const int old = atomicAdd(&arrivals[p], 1);
+    s_last = (old == n_splits - 1);
+    if (s_last) arrivals[p] = 0;  // leave the counter ready for the next call
+  }
+  lds_barrier();
+  KVS_ATTN_TRACE(5);
+  if (!s_last) return;
+  const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
+  for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
+    float mt = kNegBig;
+    for (int s = lane; s < n_splits; s += kWave) mt = fmaxf(mt, load_published(&pml[((size_t)s * QPK + h) * 2]));
+    mt = allreduce_lanes<OpMax, 1, kWave>(mt);
+    float lt = 0.f;
+    for (int s = lane; s < n_splits; s += kWave) {
+      const float w = __builtin_amdgcn_exp2f(load_published(&pml[((size_t)s * QPK + h) * 2]) - mt);
+      s_cw[h][s] = w;
+      lt = fmaf(w, load_published(&pml[((size_t)s * QPK + h) * 2 + 1]), lt);
+    }
+    lt = allreduce_lanes<OpSum, 1, kWave>(lt);
+    if (lane == 0) s_cl[h] = lt;
+  }
+  lds_barrier();
+  const float* ppo = part_o + (size_t)p * n_splits * QPK * D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {
+    const int h = i / D;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 4 <= n_splits; s += 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[j] = fmaf(s_cw[h][s + j], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
+    }
+    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[h][s], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
+    const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
+    if constexpr (E::kBytes == 2) op[i] = float_to_bf16_bits(r);
+    else op[i] = r;
+  }
+}
+
+}  // namespace kvs

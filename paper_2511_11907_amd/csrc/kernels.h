@@ -22,6 +22,15 @@ constexpr int kAttnWgThreads = KVS_ATTN_THREADS;
 constexpr int kAttnUnitsPerWave = 4;  // (K,V) load pairs a wave keeps in flight (5: no gain, 6: spills)
 constexpr int kAttnUnitsPerWgStep = (kAttnWgThreads / 64) * kAttnUnitsPerWave;
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
+// The matrix-core attention kernel (bf16, d = 128) takes over from this many query heads
+// per KV head on (measured: level with the vector-ALU kernel at 1 and 2, 5 % faster at 3,
+// 12 % at 4, 20 % at 5, 45 % at 7 and 8), with one workgroup per compute unit as its target
+// (swept 128 ... 1024: 256 is best at 32K and 128K contexts).
+#ifndef KVS_ATTN_MFMA_MIN_QPK
+#define KVS_ATTN_MFMA_MIN_QPK 3
+#endif
+constexpr int kAttnMfmaMinHeadsPerKv = KVS_ATTN_MFMA_MIN_QPK;
+constexpr int kAttnMfmaTargetWgs = 256;
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
 constexpr int kMetaMfmaTargetWgs = 1024;         // workgroups of the matrix-core metadata kernel
@@ -84,6 +93,13 @@ hipError_t launch_predict(const kvs_params& p, const Plan& pl, const void* q, co
 hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int32_t* idx,
                        int* hist, hipStream_t st);
 hipError_t launch_attn(const kvs_params& p, const Plan& pl, const void* q, const void* K,
+                       const void* V, const int32_t* idx, float* part_ml, float* part_o,
+                       void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
+                       hipStream_t st);
+// Matrix-core variant of the attention kernel (bf16 keys/values, d = 128): whether it is
+// the one to run for these parameters, and its launch (same arguments as launch_attn).
+bool attn_mfma_applies(const kvs_params& p, const Plan& pl);
+hipError_t launch_attn_mfma(const kvs_params& p, const Plan& pl, const void* q, const void* K,
                        const void* V, const int32_t* idx, float* part_ml, float* part_o,
                        void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
                        hipStream_t st);
