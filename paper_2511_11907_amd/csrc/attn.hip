@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
         ws.l[wave][h] = l[h];
       }
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) ws.o[wave][h][c * EPL + e] = o[h][e];
+      for (int e = 0; e < EPL; ++e) ws.o[wave][AttnWaveStates<D, QPK>::pos(h, c * EPL + e)] = o[h][e];
     }
   }
   attn_merge_and_finish<E, D, QPK>(ws, part_ml, part_o,

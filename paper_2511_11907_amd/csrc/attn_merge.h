@@ -41,12 +41,22 @@ inline int attn_units_per_split_with_buffer(const Plan& pl, int units) {
 
 // Per-wave states as the first half leaves them in LDS: for wave w and head h the running
 // max m, the sum l of 2^(z - m) and the accordingly weighted sum o of value rows.
+//
+// o is stored with the heads innermost - element (h, d) of a wave at d * QPK + h - plus a
+// pad after every 32 values of d that moves consecutive blocks 16 banks apart.  The merge
+// then reads consecutive words; the matrix-core kernel, whose store instructions have lane
+// (h, g) write d = 32 g + const, hits 16 g + h: a different bank for every active lane
+// (with the plain [h][d] layout all of them fell on two banks, 1.6 us per workgroup).  The
+// partial results in the workspace use the same heads-innermost order (without the pads).
 template <int D, int QPK>
 struct AttnWaveStates {
+  static constexpr int kPad = (QPK % 2 == 0) ? 16 : 48;  // (32 * QPK + kPad) % 64 == 16
+  static constexpr int kWords = QPK * D + (D / 32) * kPad;
+  static __device__ __forceinline__ int pos(int h, int d) { return d * QPK + h + (d / 32) * kPad; }
   float m[kAttnWaves][QPK];
   float l[kAttnWaves][QPK];
   float w[kAttnWaves][QPK];  // scratch of the merge
-  float o[kAttnWaves][QPK][D];
+  float o[kAttnWaves][kWords];
 };
 
 // Every lane of the workgroup calls this after its wave's state is written to `ws` (no
@@ -79,16 +89,17 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   }
   lds_barrier();
   float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
-  for (int i = tid; i < QPK * D; i += kAttnThreads) {
-    const int h = i / D, dd = i % D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {  // i = d * QPK + h
+    const int h = i % QPK, dd = i / QPK;
+    const int at = AttnWaveStates<D, QPK>::pos(h, dd);
     float acc = 0.f;
-    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][h][dd], acc);
+    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][at], acc);
     publish_store(&po[i], acc);
   }
 
   // ---- the last workgroup of the problem merges the splits ------------------------
   __shared__ int s_last;
-  __shared__ float s_cw[QPK][kAttnMaxSplits];  // weight of each split, per head
+  __shared__ float s_cw[kAttnMaxSplits][QPK];  // weight of each split, per head
   __shared__ float s_cl[QPK];                  // merged softmax denominators
   KVS_ATTN_TRACE(3);
   publish_complete_and_barrier();  // the partials are out before the arrival is announced
@@ -109,7 +120,7 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
     float lt = 0.f;
     for (int s = lane; s < n_splits; s += kWave) {
       const float w = __builtin_amdgcn_exp2f(load_published(&pml[((size_t)s * QPK + h) * 2]) - mt);
-      s_cw[h][s] = w;
+      s_cw[s][h] = w;
       lt = fmaf(w, load_published(&pml[((size_t)s * QPK + h) * 2 + 1]), lt);
     }
     lt = allreduce_lanes<OpSum, 1, kWave>(lt);
@@ -117,19 +128,19 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   }
   lds_barrier();
   const float* ppo = part_o + (size_t)p * n_splits * QPK * D;
-  for (int i = tid; i < QPK * D; i += kAttnThreads) {
-    const int h = i / D;
+  for (int i = tid; i < QPK * D; i += kAttnThreads) {  // i = d * QPK + h
+    const int h = i % QPK, dd = i / QPK;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     int s = 0;
     for (; s + 4 <= n_splits; s += 4) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        acc[j] = fmaf(s_cw[h][s + j], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
+        acc[j] = fmaf(s_cw[s + j][h], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
     }
-    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[h][s], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
+    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[s][h], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
     const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
-    if constexpr (E::kBytes == 2) op[i] = float_to_bf16_bits(r);
-    else op[i] = r;
+    if constexpr (E::kBytes == 2) op[h * D + dd] = float_to_bf16_bits(r);
+    else op[h * D + dd] = r;
   }
 }
 

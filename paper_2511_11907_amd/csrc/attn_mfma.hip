@@ -243,7 +243,7 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
 #pragma unroll
     for (int bb = 0; bb < 8; ++bb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ws.o[wave][c][8 * (4 * g + i) + bb] = o[bb][i];
+      for (int i = 0; i < 4; ++i) ws.o[wave][AttnWaveStates<D, QPK>::pos(c, 8 * (4 * g + i) + bb)] = o[bb][i];
   }
   attn_merge_and_finish<BF16Elem, D, QPK>(ws, part_ml, part_o,
                                           out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D, arrivals,
