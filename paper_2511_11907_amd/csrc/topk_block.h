@@ -7,12 +7,10 @@
 //      names the bin that holds T and how many keys lie in higher bins.  The histogram
 //      is either built here or was accumulated in global memory by the kernel that
 //      produced the scores;
-//   2. the keys of that bin - a few per cent of all keys for scores of similar
-//      magnitude - are gathered in LDS, one per lane, and the remaining 20 bits are
-//      settled two per round by counting, with wave ballots, how many candidates are
-//      >= each of three pivots.  If the bin holds more keys than there are lanes (many
-//      equal or tightly clustered scores) the same descent runs over every lane's
-//      register-resident slice instead;
+//   2. the remaining 20 bits are settled by three more, small histograms (8, 8 and 4
+//      bits) in LDS, each over the keys that agree with the prefix found so far - a few
+//      per cent of all keys after step 1, a handful after that - and each scanned by
+//      one wave;
 //   3. one block-wide prefix sum over packed (greater, equal) counts gives every
 //      selected index its final position.
 // Integer work only: the result is a deterministic function of the scores.
@@ -34,12 +32,14 @@ constexpr int kTopkBins = 4096;      // histogram over key >> kTopkLowBits
 constexpr int kTopkLowBits = 20;
 constexpr int kTopkBinsPerLane = kTopkBins / kTopkThreads;
 
+constexpr int kTopkLevels = 3;       // histogram levels below the first: 8 + 8 + 4 bits
+static_assert(kTopkLowBits == 8 + 8 + 4, "the lower levels must cover the low bits");
+
 struct TopkShared {
   int hist[kTopkBins];              // top-12-bit histogram when it is built here
-  uint32_t cand[kTopkThreads];      // keys of the bin that holds T
-  int cnt[2][kTopkWaves][16];       // per-wave pivot counts, double-buffered by round
+  int sub[kTopkLevels][256];        // histograms of the lower levels
   uint32_t wave_tot[kTopkWaves];    // prefix-sum scratch
-  int sel_bin, sel_above, n_cand;
+  int sel_bin, sel_above;
 };
 
 // float -> uint32 whose unsigned order equals the float order; -0 is folded into +0
@@ -74,36 +74,6 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, TopkShared&
 #pragma unroll
   for (int w = 0; w < kTopkWaves; ++w) base += (w < wave) ? sh.wave_tot[w] : 0u;
   return base + incl - v;
-}
-
-// One round of the descent.  c1..c3: this wave's counts of the keys it scans that are >=
-// the three pivots; `base`: keys known to lie above everything that is being scanned.
-// Invariant kept: at least M keys are >= prefix, and `above` (< M) keys are >= the upper
-// end of the current range.  Returns true if a pivot cut off exactly M keys.
-__device__ __forceinline__ bool descend(TopkShared& sh, int round, int c1, int c2, int c3, int base,
-                                        int M, uint32_t p1, uint32_t p2, uint32_t p3,
-                                        uint32_t& prefix, int& above) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int buf = round & 1;
-  if (lane == 0) {
-    sh.cnt[buf][wave][0] = c1;
-    sh.cnt[buf][wave][1] = c2;
-    sh.cnt[buf][wave][2] = c3;
-  }
-  lds_barrier();
-  int C1 = base, C2 = base, C3 = base;
-#pragma unroll
-  for (int w = 0; w < kTopkWaves; ++w) {
-    C1 += sh.cnt[buf][w][0];
-    C2 += sh.cnt[buf][w][1];
-    C3 += sh.cnt[buf][w][2];
-  }
-  int at;  // keys at or above the new lower end
-  if (C3 >= M) { prefix = p3; at = C3; }
-  else if (C2 >= M) { prefix = p2; above = C3; at = C2; }
-  else if (C1 >= M) { prefix = p1; above = C2; at = C1; }
-  else { above = C1; at = -1; }
-  return at == M;
 }
 
 // All kTopkThreads lanes of the workgroup must call this with the same arguments.
@@ -177,11 +147,9 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     for (int c = 0; c < kTopkBinsPerLane; ++c) asm volatile("" : "+v"(mine[c]));
   }
   // ---- 1. histogram of the top 12 bits ------------------------------------------------
-  if (hist_global) {
-    if (tid == 0) sh.n_cand = 0;
-  } else {
+  if (tid < kTopkLevels * 256) (&sh.sub[0][0])[tid] = 0;  // (ordered before their use by the barriers of step 1)
+  if (!hist_global) {
     for (int i = tid; i < kTopkBins; i += kTopkThreads) sh.hist[i] = 0;
-    if (tid == 0) sh.n_cand = 0;
     lds_barrier();
 #pragma unroll
     for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
@@ -217,97 +185,67 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
   int above = sh.sel_above;  // keys in higher bins; the M-th key is in `bin`
 
   KVS_TOPK_TRACE(3);
-  // ---- 2. settle the low 20 bits ----------------------------------------------------------
-  // gather the keys of the bin, one slot each (order is irrelevant here): each wave
-  // counts its candidates, reserves a range with one LDS atomic, then fills it
-  {
-    int wave_total = 0;
+  // ---- 2. settle the low 20 bits: three more histogram levels (8, 8 and 4 bits) ---------------
+  // Only the keys that agree with the prefix found so far take part - a few per cent after
+  // the first level, a handful after the second - so the LDS atomics are almost free of
+  // contention; wave 0 scans the (at most 256) bins of a level from the top with one DPP
+  // prefix sum.  Two barriers per level, nothing to gather, no limit on how many keys tie.
+#pragma unroll
+  for (int level = 0; level < kTopkLevels; ++level) {
+    constexpr int kShift[kTopkLevels] = {12, 4, 0};
+    constexpr int kBits[kTopkLevels] = {8, 8, 4};
+    const int shift = kShift[level], bits = kBits[level], nbins = 1 << bits;
+    const uint32_t hi = prefix >> (shift + bits);
 #pragma unroll
     for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
       if (c0 < kpt) {  // uniform
 #pragma unroll
-        for (int j = c0; j < c0 + kTopkChunk; ++j)
-          wave_total += __popcll(__ballot((key[j] >> kTopkLowBits) == bin));  // padding keys are 0: bin 0 only
-      }
-    }
-    int base = 0;
-    if (wave_total != 0) {  // uniform
-      if (lane == 0) base = atomicAdd(&sh.n_cand, wave_total);
-      base = __builtin_amdgcn_readfirstlane(base);
-#pragma unroll
-      for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-        if (c0 < kpt) {  // uniform
-#pragma unroll
-          for (int j = c0; j < c0 + kTopkChunk; ++j) {
-            const bool is_cand = (key[j] >> kTopkLowBits) == bin;
-            const unsigned long long m = __ballot(is_cand);
-            const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
-            if (is_cand && pos < kTopkThreads) sh.cand[pos] = key[j];
-            base += __popcll(m);
-          }
-        }
-      }
-    }
-  }
-  lds_barrier();
-  const int n_cand = sh.n_cand;
-  KVS_TOPK_TRACE(4);
-  const int bin_above = above;
-  bool cut = (above + n_cand == M) && prefix != 0u;  // the whole bin is selected: nothing to settle
-  if (!cut) {
-    if (n_cand <= kTopkThreads) {
-      // one candidate per lane; four bits per round: 15 pivots, counted with ballots,
-      // summed over the waves by lanes 0..14 of every wave
-      const uint32_t ck = (tid < n_cand) ? sh.cand[tid] : 0u;  // 0 is below every pivot
-#pragma unroll 1
-      for (int shift = kTopkLowBits - 4; shift >= 0; shift -= 4) {
-        const int buf = (shift >> 2) & 1;
-#pragma unroll
-        for (int i = 1; i < 16; ++i) {
-          const int c = __popcll(__ballot(ck >= (prefix | ((uint32_t)i << shift))));
-          if (lane == 0) sh.cnt[buf][wave][i - 1] = c;
-        }
-        lds_barrier();
-        int tot = bin_above;  // lane l (< 15): keys >= pivot l+1, counting those in higher bins
-        if (lane < 15) {
-#pragma unroll
-          for (int w = 0; w < kTopkWaves; ++w) tot += sh.cnt[buf][w][lane];
-        }
-        // totals fall as the pivot rises: the pivots with >= M keys form a prefix
-        const int i = __popcll(__ballot(lane < 15 && tot >= M));  // 0..15, uniform
-        const int t_next = __builtin_amdgcn_readlane(tot, min(i, 14));
-        const int t_here = __builtin_amdgcn_readlane(tot, max(i - 1, 0));
-        if (i < 15) above = t_next;          // keys >= the next pivot lie above the new range
-        if (i > 0) {
-          prefix |= (uint32_t)i << shift;
-          if (t_here == M) { cut = true; break; }  // uniform
-        }
-      }
-    } else {
-#pragma unroll 1
-      for (int shift = kTopkLowBits - 2; shift >= 0; shift -= 2) {
-        const uint32_t p1 = prefix | (1u << shift), p2 = prefix | (2u << shift), p3 = prefix | (3u << shift);
-        int c1 = 0, c2 = 0, c3 = 0;
-#pragma unroll
-        for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-          if (c0 < kpt) {  // uniform
-#pragma unroll
-            for (int j = c0; j < c0 + kTopkChunk; ++j) {
-              c1 += __popcll(__ballot(key[j] >= p1));
-              c2 += __popcll(__ballot(key[j] >= p2));
-              c3 += __popcll(__ballot(key[j] >= p3));
+        for (int j = c0; j < c0 + kTopkChunk; ++j) {
+          const bool real = (j < kpt) && (first + j < NG);
+          const bool hit = real && (key[j] >> (shift + bits)) == hi;
+          const int sub_bin = (int)((key[j] >> shift) & (uint32_t)(nbins - 1));
+          const unsigned long long hits = __ballot(hit);
+          if (hits != 0ull) {  // uniform
+            // many equal scores would pile onto one counter: if every hit of the wave is in
+            // the same bin, one lane adds them all
+            const int first_hit = __builtin_ctzll(hits);
+            const int bin0 = __builtin_amdgcn_readlane(sub_bin, first_hit);
+            if (__ballot(hit && sub_bin == bin0) == hits) {
+              if (lane == first_hit) atomicAdd(&sh.sub[level][bin0], __popcll(hits));
+            } else if (hit) {
+              atomicAdd(&sh.sub[level][sub_bin], 1);
             }
           }
         }
-        if (descend(sh, shift >> 1, c1, c2, c3, 0, M, p1, p2, p3, prefix, above)) { cut = true; break; }
       }
     }
+    lds_barrier();
+    if (wave == 0) {
+      int cnt[4];  // bins nbins-1-4*lane downwards
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int bin_c = nbins - 1 - (lane * 4 + c);
+        cnt[c] = bin_c >= 0 ? sh.sub[level][bin_c] : 0;
+      }
+      const uint32_t tot = (uint32_t)(cnt[0] + cnt[1] + cnt[2] + cnt[3]);
+      int above_me = above + (int)(wave_scan_dpp(tot) - tot);  // keys above my first bin
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (above_me < M && M <= above_me + cnt[c]) {
+          sh.sel_bin = nbins - 1 - (lane * 4 + c);
+          sh.sel_above = above_me;
+        }
+        above_me += cnt[c];
+      }
+    }
+    lds_barrier();
+    prefix |= (uint32_t)sh.sel_bin << shift;
+    above = sh.sel_above;
   }
   KVS_TOPK_TRACE(5);
   // Selected: keys > T, plus the first `need` keys equal to T in index order.
-  // After a clean cut everything >= prefix is selected: T = prefix - 1 and need = 0.
-  const uint32_t T = cut ? prefix - 1u : prefix;
-  const int need = cut ? 0 : M - above;
+  const uint32_t T = prefix;   // the M-th largest key
+  const int need = M - above;  // `above` keys are greater than T
 
   // ---- 3. ordered compaction -------------------------------------------------------------
   uint32_t packed = 0;  // low half: keys > T, high half: keys == T
