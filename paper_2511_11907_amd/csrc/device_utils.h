@@ -96,6 +96,35 @@ __device__ __forceinline__ float load_as_float(const void* base, int is_bf16, si
   return is_bf16 ? bf16_bits_to_float(((const uint16_t*)base)[i]) : ((const float*)base)[i];
 }
 
+// Sum over `count` (<= kMaxSummed) elements base[first + j * stride] as fp32, in two halves:
+// request() issues all the loads, sum() adds them up.  Written as a loop that adds as it
+// goes, every load would be waited for on its own, one memory latency after the other; and
+// with other requests placed between the two halves this latency overlaps theirs.
+constexpr int kMaxSummed = 8;
+struct StridedSum {
+  uint32_t raw[kMaxSummed];
+  __device__ __forceinline__ void request(const void* base, int is_bf16, size_t first, size_t stride, int count) {
+    if (is_bf16) {  // uniform
+#pragma unroll
+      for (int j = 0; j < kMaxSummed; ++j)
+        raw[j] = ((const uint16_t*)base)[first + (size_t)min(j, count - 1) * stride];
+    } else {
+#pragma unroll
+      for (int j = 0; j < kMaxSummed; ++j)
+        raw[j] = ((const uint32_t*)base)[first + (size_t)min(j, count - 1) * stride];
+    }
+  }
+  __device__ __forceinline__ float sum(int is_bf16, int count) const {
+    float total = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxSummed; ++j) {
+      const float v = is_bf16 ? bf16_bits_to_float(raw[j]) : __uint_as_float(raw[j]);
+      total += (j < count) ? v : 0.f;
+    }
+    return total;
+  }
+};
+
 // ---- workgroup barrier for LDS traffic only ----------------------------------------------
 // __syncthreads() also waits for every outstanding global load and store of the wave,
 // which serialises the memory latency the kernels work to overlap (prefetched tiles,

@@ -118,14 +118,12 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
   const int pj = tid % R, psl = tid / R;
   const int span = d / NSL;
   const bool project = (qlr == nullptr);  // uniform: false when the low-rank query is given
-  float qsum_part = 0.f;
+  StridedSum qheads;
   float a_reg[kSpanMax];
   float qr[EPL];
   if (project) {
-    if (tid < d) {
-      for (int hh = 0; hh < q_per_kv; ++hh)
-        qsum_part += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + tid);
-    }
+    // the query heads of this KV head, element tid of each (lanes beyond d repeat the last)
+    qheads.request(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv) * d + min(tid, d - 1), d, q_per_kv);
     const float* Ak = A + (size_t)k * d * R;
 #pragma unroll
     for (int i = 0; i < kSpanMax; ++i)
@@ -143,7 +141,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(
 
   if (project) {
     // ---- low-rank query vector of this KV head (head-summed) --------------------
-    if (tid < d) s_qsum[tid] = qsum_part;
+    if (tid < d) s_qsum[tid] = qheads.sum(q_is_bf16, q_per_kv);
     lds_barrier();
     float acc = 0.f;
 #pragma unroll
@@ -252,10 +250,9 @@ __global__ __launch_bounds__(kProjectThreads) void project_query_kernel(
   const int n_q_heads = n_kv_heads * q_per_kv;
   for (int i = tid; i < L; i += kProjectThreads) {
     const int k = i / d, e = i % d;
-    float sum = 0.f;
-    for (int hh = 0; hh < q_per_kv; ++hh)
-      sum += load_as_float(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv + hh) * d + e);
-    s_qcat[i] = sum;
+    StridedSum heads;
+    heads.request(q, q_is_bf16, ((size_t)b * n_q_heads + (size_t)k * q_per_kv) * d + e, d, q_per_kv);
+    s_qcat[i] = heads.sum(q_is_bf16, q_per_kv);
   }
   lds_barrier();
   const int j = tid % R, sl = tid / R;
