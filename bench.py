@@ -208,10 +208,12 @@ def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bo
 
 def time_kernels(wl: Workload, reps: int) -> dict:
     """Average duration of each of the step's three kernels from HIP events on the launch
-    stream: `reps` back-to-back launches over the rotating copies between two events, through
-    the split entry points (the same kernels kvs_decode_step launches).  The figure includes
-    the gap between consecutive launches (about a microsecond), so it is an upper bound on
-    the kernel's own duration; the rocprofv3 kernel trace under profiles/ has the latter.
+    stream: `reps` back-to-back launches over the rotating copies, through the split entry
+    points (the same kernels kvs_decode_step launches), replayed as one captured graph
+    between two events, so that the host's launch cost (longer than the small kernels) is
+    not in the figure.  What remains beside the kernel's own duration is the gap between
+    consecutive launches on the device (about a microsecond); the rocprofv3 kernel trace
+    under profiles/ has the durations alone.
     The selection kernel consumes the histogram the prediction kernel leaves behind, so it
     is timed as (prediction + selection) minus prediction."""
     torch, kv, p = wl.torch, wl.kv, wl.p
@@ -220,10 +222,15 @@ def time_kernels(wl: Workload, reps: int) -> dict:
         for i in range(min(reps, len(wl.slots))):
             fn(wl.slots[i % len(wl.slots)])
         torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(reps):
+                fn(wl.slots[i % len(wl.slots)])
+        g.replay()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for i in range(reps):
-            fn(wl.slots[i % len(wl.slots)])
+        g.replay()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps   # us
