@@ -1,6 +1,9 @@
 // Attention over the selected KV groups only (Sec. 3.4: the attention kernel consumes
 // the groups the predictor chose; here they are gathered straight from the full
-// K/V in HBM, which stands in for the paper's preload buffer).
+// K/V in HBM, which stands in for the paper's preload buffer).  This is the vector-ALU
+// kernel, for every layout the matrix-core one (attn_mfma.hip: bf16, d = 128, three or
+// more query heads per KV head) does not take: fp32 keys and values, d = 64, one or two
+// heads per KV head.  launch_attn at the end of the file picks between the two.
 //
 // Split-K flash-decode.  A (sequence, KV head) problem owns M groups = M*G tokens;
 // the token list is cut into "units" of one wave-wide 16-byte-per-lane load

@@ -91,11 +91,6 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
-// Scalar load of one stored element as fp32 (runtime dtype; cold paths only).
-__device__ __forceinline__ float load_as_float(const void* base, int is_bf16, size_t i) {
-  return is_bf16 ? bf16_bits_to_float(((const uint16_t*)base)[i]) : ((const float*)base)[i];
-}
-
 // Sum over `count` (<= kMaxSummed) elements base[first + j * stride] as fp32, in two halves:
 // request() issues all the loads, sum() adds them up.  Written as a loop that adds as it
 // goes, every load would be waited for on its own, one memory latency after the other; and
