@@ -114,14 +114,28 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   if (!s_last) return;
   const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
   for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
+    // (m, l) of this lane's splits, all requested at once: one memory latency
+    constexpr int kPerLane = kAttnMaxSplits / kWave;
+    float m_s[kPerLane], l_s[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+      const size_t at = ((size_t)min(lane + j * kWave, n_splits - 1) * QPK + h) * 2;
+      m_s[j] = load_published(&pml[at]);
+      l_s[j] = load_published(&pml[at + 1]);
+    }
     float mt = kNegBig;
-    for (int s = lane; s < n_splits; s += kWave) mt = fmaxf(mt, load_published(&pml[((size_t)s * QPK + h) * 2]));
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) mt = (lane + j * kWave < n_splits) ? fmaxf(mt, m_s[j]) : mt;
     mt = allreduce_lanes<OpMax, 1, kWave>(mt);
     float lt = 0.f;
-    for (int s = lane; s < n_splits; s += kWave) {
-      const float w = __builtin_amdgcn_exp2f(load_published(&pml[((size_t)s * QPK + h) * 2]) - mt);
-      s_cw[s][h] = w;
-      lt = fmaf(w, load_published(&pml[((size_t)s * QPK + h) * 2 + 1]), lt);
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+      const int s = lane + j * kWave;
+      if (s < n_splits) {
+        const float w = __builtin_amdgcn_exp2f(m_s[j] - mt);
+        s_cw[s][h] = w;
+        lt = fmaf(w, l_s[j], lt);
+      }
     }
     lt = allreduce_lanes<OpSum, 1, kWave>(lt);
     if (lane == 0) s_cl[h] = lt;
@@ -131,13 +145,21 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   for (int i = tid; i < QPK * D; i += kAttnThreads) {  // i = d * QPK + h
     const int h = i % QPK, dd = i / QPK;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 4 <= n_splits; s += 4) {
+    // kBatch splits at a time, all their loads requested before the first is used: these
+    // loads go past the caches, and four at a time (the first version) meant one full
+    // memory latency per four splits - 8 in a row at 32 splits per problem
+    constexpr int kBatch = 16;
+    for (int s0 = 0; s0 < n_splits; s0 += kBatch) {
+      float v[kBatch];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[j] = fmaf(s_cw[s + j][h], load_published(&ppo[(size_t)(s + j) * QPK * D + i]), acc[j]);
+      for (int j = 0; j < kBatch; ++j)
+        v[j] = load_published(&ppo[(size_t)min(s0 + j, n_splits - 1) * QPK * D + i]);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const float w = (s0 + j < n_splits) ? s_cw[min(s0 + j, n_splits - 1)][h] : 0.f;
+        acc[j & 3] = fmaf(w, v[j], acc[j & 3]);
+      }
     }
-    for (; s < n_splits; ++s) acc[0] = fmaf(s_cw[s][h], load_published(&ppo[(size_t)s * QPK * D + i]), acc[0]);
     const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
     if constexpr (E::kBytes == 2) op[h * D + dd] = float_to_bf16_bits(r);
     else op[h * D + dd] = r;
