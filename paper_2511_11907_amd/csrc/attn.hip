@@ -23,20 +23,9 @@
 #include "device_utils.h"
 #include "kernels.h"
 
-// Phase timestamps for the debugging harness (compiled only with -DKVS_ATTN_TRACE_BUILD):
-// one row of 8 wall-clock stamps per workgroup.
-#ifdef KVS_ATTN_TRACE_BUILD
-__device__ long long g_attn_trace[1 << 16];
-#define KVS_ATTN_TRACE(i)                                                                           \
-  do {                                                                                               \
-    if (threadIdx.x == 0) g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)) & 0xFFFF] = wall_clock64(); \
-  } while (0)
-extern "C" int kvs_debug_attn_trace(long long* host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), sizeof(long long) * (size_t)n);
-}
-#endif
-
 #include "attn_merge.h"
+
+KVS_ATTN_TRACE_ACCESSOR(kvs_debug_attn_trace)
 
 namespace kvs {
 

@@ -8,8 +8,21 @@
 #include "device_utils.h"
 #include "kernels.h"
 
-#ifndef KVS_ATTN_TRACE
-#define KVS_ATTN_TRACE(i)  // phase timestamps, only defined by the debugging build
+// Phase timestamps for the debugging harness (compiled only with -DKVS_ATTN_TRACE_BUILD): one
+// row of 8 wall-clock stamps per workgroup, in an array of the including source file's own.
+#ifdef KVS_ATTN_TRACE_BUILD
+static __device__ long long g_attn_trace[1 << 16];
+#define KVS_ATTN_TRACE(i)                                                                           \
+  do {                                                                                               \
+    if (threadIdx.x == 0) g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)) & 0xFFFF] = wall_clock64(); \
+  } while (0)
+#define KVS_ATTN_TRACE_ACCESSOR(name)                                                               \
+  extern "C" int name(long long* host, int n) {                                                     \
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), sizeof(long long) * (size_t)n); \
+  }
+#else
+#define KVS_ATTN_TRACE(i)
+#define KVS_ATTN_TRACE_ACCESSOR(name)
 #endif
 
 namespace kvs {

@@ -30,6 +30,8 @@
 // maximum, the denominator and the rescaling of the accumulators stay in the lane.
 #include "attn_merge.h"
 
+KVS_ATTN_TRACE_ACCESSOR(kvs_debug_attn_mfma_trace)
+
 namespace kvs {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -68,6 +70,12 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // (tells the compiler it is uniform)
   const int split = blockIdx.x, p = blockIdx.y;
+  KVS_ATTN_TRACE(0);
+#ifdef KVS_ATTN_TRACE_BUILD
+  if (threadIdx.x == 0)  // where the workgroup runs: XCC id (hwreg 20), HW id (hwreg 4)
+    g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + 7) & 0xFFFF] =
+        ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
   const int b = p / n_kv_heads, k = p % n_kv_heads;
   const int n_q_heads = n_kv_heads * QPK;
   const int c = lane & 15;  // head (logits, output), token of the tile (keys), d block (values)
@@ -216,6 +224,7 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
   find_groups(ub0, rows);
   find_rows(ub0, rows);
   if constexpr (PAGED) find_groups(ub0 + kStep, ahead);
+  KVS_ATTN_TRACE(1);
   for (int ub = ub0; ub < u1; ub += kStep) {
     request(ub, rows, kv, vv);
     if constexpr (PAGED) {
@@ -232,6 +241,7 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
     }
   }
 
+  KVS_ATTN_TRACE(2);
   // ---- this wave's state of head c: add up the four slices' denominators ----------------
   l += xor_lane<16>(l);
   l += xor_lane<32>(l);
@@ -248,6 +258,7 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
   attn_merge_and_finish<BF16Elem, D, QPK>(ws, part_ml, part_o,
                                           out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D, arrivals,
                                           p, split, n_splits);
+  KVS_ATTN_TRACE(6);
 }
 
 namespace {
