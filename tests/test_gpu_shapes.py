@@ -138,6 +138,17 @@ def test_all_negative_scores_with_padded_groups():
             H.check_index_margin(idx_h[b, k], ref2["gs"][b, k], ref2["boundary"][b, k], f"negative b={b} k={k}")
 
 
+def test_one_problem_cut_into_the_maximum_number_of_splits():
+    """A single (sequence, KV head) problem with 32 768 selected tokens: 256 attention
+    workgroups, i.e. as many splits as the merge can hold (four per lane of the wave that
+    weighs them, sixteen loops of the batched partial loads)."""
+    cfg = _cfg("one_problem_256_splits", "bf16", 4, 1, 128, 64, 8, 8192, 4096, B=1)
+    _say(cfg.name, H.run_and_compare(cfg, check_meta=False))
+    # the same through the vector-ALU kernel (two heads per KV head)
+    cfg2 = _cfg("one_problem_valu", "bf16", 2, 1, 128, 64, 8, 8192, 4096, B=1)
+    _say(cfg2.name, H.run_and_compare(cfg2, check_meta=False))
+
+
 # ---- the paper's operating point at full context length, oracle on sampled problems ------------
 def test_qwen3_14b_layer_32k_g12_full_size_sampled():
     """40 query / 8 KV heads, 32 760 tokens, G = 12, M = 33 (M*G = 396), batch 4."""
