@@ -36,6 +36,7 @@ constexpr int kAttnUnroll = kAttnUnitsPerWgStep / kAttnWaves;  // units (K load 
 // order behind the loads in flight and stalls the wave for a full memory latency.
 template <typename E, int QPK, int MODE>
 constexpr int attn_min_waves() {
+  if (MODE == kAttnPaged && E::kBytes == 2 && QPK >= 4) return 2;  // (its look-ahead needs the registers)
   if (QPK <= 4) return 4;
   if (QPK == 5 && (E::kBytes == 4 || MODE == kAttnPlain)) return 4;
   return 2;
@@ -125,23 +126,25 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
   // buffer are taken by the last split
   const int u1 = (split == n_splits - 1) ? units : min(units, u0 + units_per_split);
 
-  // Where the selected groups of a batch are (their indices, and through the mapping table
-  // their slots) is looked up one batch ahead, while the previous batch's keys and values
-  // are still on their way: a batch then costs one memory latency, not two in a row.
-  auto locate = [&](int ubase, int (&g)[kAttnUnroll]) {
+  // Where the selected groups of a batch are is looked up one batch ahead, while the
+  // previous batch's keys and values are still on their way: a batch then costs one memory
+  // latency, not two in a row.  With a mapping table the slot look-up depends on the group
+  // look-up; done in the same iteration it would be waited for on the spot, together with
+  // every load issued before it, so groups are found two batches ahead and slots one.
+  auto locate_groups = [&](int ubase, int (&g)[kAttnUnroll]) {
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) {
       const int tok = (ubase + u) * TPU + ts;  // position in the attended-token list
       const bool in_cache = (ubase + u < u1) && (tok < n_tok);
       g[u] = in_cache ? sel[group_of(tok)] : 0;
     }
-    if constexpr (PAGED) {
+  };
+  auto locate_slots = [&](int ubase, int (&g)[kAttnUnroll]) {  // logical group -> slot, in place
 #pragma unroll
-      for (int u = 0; u < kAttnUnroll; ++u) {
-        const int tok = (ubase + u) * TPU + ts;
-        const bool in_cache = (ubase + u < u1) && (tok < n_tok);
-        g[u] = in_cache ? tab[g[u]] : 0;  // logical group -> slot
-      }
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      const int tok = (ubase + u) * TPU + ts;
+      const bool in_cache = (ubase + u < u1) && (tok < n_tok);
+      g[u] = in_cache ? tab[g[u]] : 0;
     }
   };
   // request(ub, g, kv, vv): issue the K and V loads of the batch that starts at unit ub, whose
@@ -228,13 +231,24 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
 
   constexpr int kStep = kAttnWaves * kAttnUnroll;
   const int ub0 = u0 + wave * kAttnUnroll;
-  int grp[kAttnUnroll], grp_next[kAttnUnroll];
+  int grp[kAttnUnroll], grp_next[kAttnUnroll], ahead[kAttnUnroll];
   uint4 kv[kAttnUnroll], vv[kAttnUnroll];
-  locate(ub0, grp);
+  locate_groups(ub0, grp);
+  if constexpr (PAGED) {
+    locate_slots(ub0, grp);
+    locate_groups(ub0 + kStep, ahead);
+  }
   KVS_ATTN_TRACE(1);
   for (int ub = ub0; ub < u1; ub += kStep) {
     request(ub, grp, kv, vv);
-    locate(ub + kStep, grp_next);  // (past the end: nothing is read)
+    if constexpr (PAGED) {
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) grp_next[u] = ahead[u];  // found an iteration ago
+      locate_slots(ub + kStep, grp_next);
+      locate_groups(ub + 2 * kStep, ahead);  // (past the end: nothing is read)
+    } else {
+      locate_groups(ub + kStep, grp_next);   // (past the end: nothing is read)
+    }
     consume(ub, kv, vv);
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u) grp[u] = grp_next[u];
