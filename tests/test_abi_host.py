@@ -204,3 +204,19 @@ def test_binding_refuses_host_tensors():
     q = torch.zeros(1, 32, 128, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         kv.kvs_predict_select(p, q, q, q, q, None, None)
+
+
+def test_reciprocal_division_used_by_the_attention_kernels_is_exact():
+    """The attention kernels turn a position of the attended-token list into its group with
+    one multiply-high by floor(2^32 / G) + 1 when G is not a power of two.  That equals
+    position // G for every position below 2^28 / G; the largest position the library can
+    see is 32768 groups * 16 tokens + 256 buffer tokens."""
+    import numpy as np
+    top = 32768 * 16 + 256 + 64
+    pos = np.arange(top, dtype=np.uint64)
+    edge = np.array([2 ** 28 // 16 - 1], dtype=np.uint64)
+    for G in (3, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15):
+        recip = np.uint64((1 << 32) // G + 1)
+        assert recip < (1 << 32)
+        for x in (pos, edge):
+            assert np.array_equal((x * recip) >> np.uint64(32), x // np.uint64(G)), G
