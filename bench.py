@@ -169,7 +169,11 @@ class Workload:
 def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bool = False) -> float:
     """Seconds for exactly `steps` steps (after `warmup` untimed ones)."""
     torch = wl.torch
-    n = len(wl.slots) if wl.layers_per_step == 1 else 1   # steps per rotation
+    # steps per captured graph: one rotation over the copies, and at least 24 so that the
+    # launch of the graph itself stays a small part of a replay
+    # (layer-ahead: exactly one rotation, so that no copy - standing in for a layer - is used
+    # twice inside a graph and has to wait for its own previous use)
+    n = 1 if wl.layers_per_step != 1 else len(wl.slots) * (1 if layer_ahead else max(1, -(-24 // len(wl.slots))))
     if mode == "eager":
         wl.run(warmup, layer_ahead)
         torch.cuda.synchronize()
