@@ -56,6 +56,11 @@ CASES = [
 ]
 
 
+# seeded random draws from the supported shape space (the same ones the plain path is tested on)
+from test_gpu_random_shapes import _draw  # noqa: E402
+CASES += [_draw(_seed)[0] for _seed in (0, 3, 6, 10, 13, 17, 22, 27, 31)]
+
+
 @pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
 def test_attention_through_a_mapping_table(cfg):
     L = make_layer(cfg)

@@ -65,6 +65,13 @@ CASES = [
 ]
 
 
+# seeded random draws from the supported shape space (the same ones the plain path is tested on)
+from test_gpu_random_shapes import _draw  # noqa: E402
+for _seed in (2, 5, 7, 13, 18, 21, 26, 30):
+    _c = _draw(_seed)[0]
+    CASES.append((_c, (3 * _seed) % 17, _c.group_size + _seed % 5))
+
+
 @pytest.mark.parametrize("cfg,spare,cap", CASES, ids=[c[0].name for c in CASES])
 def test_attention_with_rolling_buffer_and_spare_capacity(cfg, spare, cap):
     L = make_layer(cfg)
