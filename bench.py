@@ -409,9 +409,11 @@ def main() -> int:
     ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
     ap.add_argument("--meta", default="same", choices=["same", "fp8"],
                     help="dtype of the compressed K cache: that of the workload, or 8-bit E4M3")
-    ap.add_argument("--layer-ahead", action="store_true",
-                    help="also time the steps issued layer-ahead (three streams); off by default so that a "
-                         "kernel trace of the default run holds no overlapped launches")
+    ap.add_argument("--layer-ahead", dest="layer_ahead", action="store_true", default=True,
+                    help="also time the steps issued layer-ahead (three streams): reported beside the serial "
+                         "figure, never instead of it (default)")
+    ap.add_argument("--no-layer-ahead", dest="layer_ahead", action="store_false",
+                    help="skip that pass, e.g. for a kernel trace that should hold no overlapped launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     # a workload's layer geometry can be changed, e.g. to that of another model of Sec. 4.1
     # (--q-heads 40 --group-size 12 --ctx-len 32760 --n-select 33: a Qwen3-14B layer at G = 12)
