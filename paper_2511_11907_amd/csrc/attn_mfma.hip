@@ -52,7 +52,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // compute unit; the mapping table's extra look-ahead does not, and a spilled register is
 // reloaded in order behind the key loads, i.e. stalls the value loads for a full latency,
 // so that mode takes what it needs)
-template <int QPK, int MODE>
+template <int QPK, int MODE, bool INTERLEAVE>
 __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const int32_t* __restrict__ idx, float* part_ml, float* part_o, uint16_t* __restrict__ out,
@@ -101,8 +101,16 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
   const uint16_t* Kr = rb_K + (size_t)p * rb_capacity * D;
   const uint16_t* Vr = rb_V + (size_t)p * rb_capacity * D;
   const int32_t* sel = idx + (size_t)(p / kv_heads_per_set) * M;
-  const int u0 = split * units_per_split;
-  const int u1 = (split == n_splits - 1) ? units : min(units, u0 + units_per_split);
+  // The units of a problem go to its splits either as one contiguous range each, or - for
+  // long problems - one workgroup step (a tile per wave) at a time, round-robin: every
+  // workgroup then walks the whole address range of the problem, and workgroups finish
+  // closer together (identical work takes a different time in different parts of a long
+  // cache: 4 % on the kernel at 128K tokens, nothing at 32K).  Either way the assignment
+  // is a fixed function of the launch, so results are reproducible bit for bit.
+  constexpr int kWgStep = kAttnWaves * kAttnUnitsPerWave;
+  const int u0 = INTERLEAVE ? split * kWgStep : split * units_per_split;
+  const int u1 = (INTERLEAVE || split == n_splits - 1) ? units : min(units, u0 + units_per_split);
+  const int kStep = INTERLEAVE ? n_splits * kWgStep : kWgStep;  // from one step of this workgroup to its next
 
   // token t of the tile that starts at unit ub is attended iff its unit belongs to this
   // split and it lies inside the list
@@ -215,7 +223,6 @@ __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn
     }
   };
 
-  constexpr int kStep = kAttnWaves * kAttnUnitsPerWave;
   const int ub0 = u0 + wave * kAttnUnitsPerWave;
   // Look-ups run ahead of the tile whose keys and values are being requested: by one tile,
   // or by two (groups) and one (mapping table) when there is a table.
@@ -278,6 +285,7 @@ hipError_t launch_mfma_qpk(const kvs_params& p, const Plan& pl, const void* q, c
   dim3 grid(pl.attn_splits, pl.problems), block(kAttnThreads);
   const int units = (p.n_select * p.group_size + rb.len + pl.kv_toks_per_unit - 1) / pl.kv_toks_per_unit;
   const int units_per_split = attn_units_per_split_with_buffer(pl, units);
+  const bool interleave = units_per_split >= kAttnInterleaveFromSteps * kAttnUnitsPerWgStep;
   auto launch = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
                        part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
@@ -285,9 +293,15 @@ hipError_t launch_mfma_qpk(const kvs_params& p, const Plan& pl, const void* q, c
                        scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity,
                        slot_table, pl.n_groups);
   };
-  if (slot_table) launch(attn_mfma_kernel<QPK, kAttnPaged>);
-  else if (rb.len > 0) launch(attn_mfma_kernel<QPK, kAttnRolling>);
-  else launch(attn_mfma_kernel<QPK, kAttnPlain>);
+  if (interleave) {
+    if (slot_table) launch(attn_mfma_kernel<QPK, kAttnPaged, true>);
+    else if (rb.len > 0) launch(attn_mfma_kernel<QPK, kAttnRolling, true>);
+    else launch(attn_mfma_kernel<QPK, kAttnPlain, true>);
+  } else {
+    if (slot_table) launch(attn_mfma_kernel<QPK, kAttnPaged, false>);
+    else if (rb.len > 0) launch(attn_mfma_kernel<QPK, kAttnRolling, false>);
+    else launch(attn_mfma_kernel<QPK, kAttnPlain, false>);
+  }
   return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@ constexpr int kSelectHistBins = 4096;          // per-problem histogram of the t
 #endif
 constexpr int kAttnMfmaMinHeadsPerKv = KVS_ATTN_MFMA_MIN_QPK;
 constexpr int kAttnMfmaTargetWgs = 256;
+constexpr int kAttnInterleaveFromSteps = 12;   // workgroup steps per split from which the splits are interleaved
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
 constexpr int kMetaMfmaTargetWgs = 1024;         // workgroups of the matrix-core metadata kernel
