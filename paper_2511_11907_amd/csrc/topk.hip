@@ -8,19 +8,24 @@
 
 namespace kvs {
 
+// SLOTS: register slots per lane, i.e. problems of up to kTopkThreads * SLOTS scores.
+template <int SLOTS>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ gs,
                                                             int32_t* __restrict__ idx, int NG,
                                                             int M, int* __restrict__ hist) {
   __shared__ TopkShared sh;
   const int p = blockIdx.x;
-  topk_block(gs + (size_t)p * NG, idx + (size_t)p * M, NG, M,
-             hist ? hist + (size_t)p * kTopkBins : nullptr, sh);
+  topk_block<SLOTS>(gs + (size_t)p * NG, idx + (size_t)p * M, NG, M,
+                    hist ? hist + (size_t)p * kTopkBins : nullptr, sh);
 }
 
 hipError_t launch_topk(const kvs_params& p, const Plan& pl, const float* gs, int32_t* idx,
                        int* hist, hipStream_t st) {
   dim3 grid(pl.sets), block(kTopkThreads);
-  hipLaunchKernelGGL(topk_kernel, grid, block, 0, st, gs, idx, pl.n_groups, p.n_select, hist);
+  if (pl.n_groups <= kTopkThreads * kTopkSmallPerLane)
+    hipLaunchKernelGGL(topk_kernel<kTopkSmallPerLane>, grid, block, 0, st, gs, idx, pl.n_groups, p.n_select, hist);
+  else
+    hipLaunchKernelGGL(topk_kernel<kTopkMaxPerLane>, grid, block, 0, st, gs, idx, pl.n_groups, p.n_select, hist);
   return hipGetLastError();
 }
 

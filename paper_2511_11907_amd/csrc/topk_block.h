@@ -6,14 +6,21 @@
 //   1. a 4096-bin histogram of the top 12 key bits (sign, exponent, 3 mantissa bits)
 //      names the bin that holds T and how many keys lie in higher bins.  The histogram
 //      is either built here or was accumulated in global memory by the kernel that
-//      produced the scores;
-//   2. the remaining 20 bits are settled by three more, small histograms (8, 8 and 4
-//      bits) in LDS, each over the keys that agree with the prefix found so far - a few
-//      per cent of all keys after step 1, a handful after that - and each scanned by
-//      one wave;
+//      produced the scores.  Every wave locates the bin by itself from the per-wave
+//      totals (one barrier);
+//   2. the keys of that bin - a few per cent of all keys - are gathered into a list in
+//      LDS, and one wave settles the remaining 20 bits with three small histograms (8, 8
+//      and 4 bits) over the list entries that agree with the prefix found so far: a
+//      single wave needs no barrier between the levels.  (A bin with more keys than
+//      the list holds - many equal scores - is settled by the same three levels over all
+//      keys, by all waves.);
 //   3. one block-wide prefix sum over packed (greater, equal) counts gives every
 //      selected index its final position.
 // Integer work only: the result is a deterministic function of the scores.
+//
+// The routine is bound by the length of its dependent instruction chain, not by the
+// number of keys (a few thousand per problem): it is written to keep that chain and the
+// number of barriers (four when the histogram is handed in) short.
 #pragma once
 
 #include "device_utils.h"
@@ -26,74 +33,189 @@ namespace kvs {
 
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / kWave;
-constexpr int kTopkMaxPerLane = 32;  // => at most 32768 scores per problem
-constexpr int kTopkChunk = 8;        // register slots handled (and loads in flight) per uniform branch
-constexpr int kTopkBins = 4096;      // histogram over key >> kTopkLowBits
+constexpr int kTopkMaxPerLane = 32;   // => at most 32768 scores per problem
+constexpr int kTopkSmallPerLane = 8;  // second instantiation, for problems of at most 8192 scores
+constexpr int kTopkChunk = 8;         // register slots handled (and loads in flight) per uniform branch
+constexpr int kTopkBins = 4096;       // histogram over key >> kTopkLowBits
 constexpr int kTopkLowBits = 20;
 constexpr int kTopkBinsPerLane = kTopkBins / kTopkThreads;
+constexpr int kTopkBinsPerWave = kTopkBins / kTopkWaves;
+constexpr int kTopkListPerLane = 16;  // keys of one bin that step 2's wave takes into registers, per lane
+constexpr int kTopkListCap = kTopkListPerLane * kWave;
 
-constexpr int kTopkLevels = 3;       // histogram levels below the first: 8 + 8 + 4 bits
+constexpr int kTopkLevels = 3;        // histogram levels below the first: 8 + 8 + 4 bits
+constexpr int kTopkLevelBins = 256;
 static_assert(kTopkLowBits == 8 + 8 + 4, "the lower levels must cover the low bits");
+static_assert(kTopkBinsPerLane == 4 && kTopkLevelBins == 4 * kWave, "histograms are read four bins per lane");
+static_assert(kTopkWaves == 16, "the prefix over the waves is taken inside one row of 16 lanes");
 
+// Histograms are stored top bin first (bin b at index size-1-b): the search runs from the
+// largest keys downwards, and a lane then reads its four bins as one 16-byte piece.
 struct TopkShared {
-  int hist[kTopkBins];              // top-12-bit histogram when it is built here
-  int sub[kTopkLevels][256];        // histograms of the lower levels
-  uint32_t wave_tot[kTopkWaves];    // prefix-sum scratch
-  int sel_bin, sel_above;
+  alignas(16) int hist[kTopkBins];                    // top-12-bit histogram
+  alignas(16) uint32_t list[kTopkListCap];            // keys of the bin that holds the M-th key
+  alignas(16) int sub[kTopkLevels][kTopkLevelBins];   // histograms of the lower levels
+  uint32_t wave_tot[2][kTopkWaves];       // per-wave totals of the two block-wide prefix sums
+  int n_listed;
+  int sel_above;                          // hand-over of a level's result and of step 2's
+  uint32_t sel_key;
 };
 
 // float -> uint32 whose unsigned order equals the float order; -0 is folded into +0
-// so that equal scores have equal keys.  Every finite score maps to a key >= 1.
+// so that equal scores have equal keys.  Keys are at least kTopkMinKey (only some NaN
+// patterns with the sign bit set are raised to it; -inf and every finite score lie
+// above), so that the key 0 of an unused register slot is below every key of a score and
+// falls into a histogram bin that no score uses.
+constexpr uint32_t kTopkMinKey = 1u << 20;
 __device__ __forceinline__ uint32_t score_key(float x) {
   const uint32_t u = __float_as_uint(x + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  const uint32_t flip = (uint32_t)((int32_t)u >> 31) | 0x80000000u;  // all bits of a negative value, the sign bit of others
+  return max(u ^ flip, kTopkMinKey);
 }
 
-// Inclusive prefix sum over the wave (lane i gets the sum of lanes 0..i), DPP only:
-// a Hillis-Steele scan inside each row of 16 lanes (shifted-in lanes read as zero),
-// then the running totals of the rows are passed on with row_bcast:15 / row_bcast:31.
-__device__ __forceinline__ uint32_t wave_scan_dpp(uint32_t v) {
-  int x = (int)v;
+// Inclusive prefix sum inside each row of 16 lanes (DPP, shifted-in lanes read as zero).
+__device__ __forceinline__ int row_scan_dpp(int x) {
   x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);  // row_shr:1
   x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);  // row_shr:2
   x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);  // row_shr:4
   x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);  // row_shr:8
-  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false); // row_bcast:15 into rows 1 and 3
-  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false); // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// Inclusive prefix sum over the wave (lane i gets the sum of lanes 0..i): the rows' scans,
+// then the running totals of the rows are passed on with row_bcast:15 / row_bcast:31.
+__device__ __forceinline__ uint32_t wave_scan_dpp(uint32_t v) {
+  int x = row_scan_dpp((int)v);
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
   return (uint32_t)x;
 }
 
-// Exclusive prefix sum across the workgroup in thread order (one barrier; wave_tot must
-// not be rewritten before the next barrier of the caller).
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, TopkShared& sh) {
+// Exclusive prefix sum across the workgroup in thread order (one barrier).  `tot` holds one
+// word per wave and must not be rewritten before the caller's next barrier.  After the
+// barrier every wave adds up the totals of the waves before it inside one row of 16 lanes.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* tot) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const uint32_t incl = wave_scan_dpp(v);
-  if (lane == kWave - 1) sh.wave_tot[wave] = incl;
+  if (lane == kWave - 1) tot[wave] = incl;
   lds_barrier();
-  uint32_t base = 0;
+  const int w = lane & (kTopkWaves - 1);
+  const int before = row_scan_dpp(w < wave ? (int)tot[w] : 0);
+  return (uint32_t)__builtin_amdgcn_readlane(before, kTopkWaves - 1) + incl - v;
+}
+
+// A lane's four bins `b` (top bin first) of a histogram whose bins before this lane's hold
+// `above_me` keys: does the M-th key from the top fall into one of them?  If so `bin_pos`
+// (position of that bin among the four) and `above` (keys in higher bins) are set.
+__device__ __forceinline__ bool topk_find_in_four(const int (&b)[4], int above_me, int M, int& bin_pos, int& above) {
+  bool found = false;
 #pragma unroll
-  for (int w = 0; w < kTopkWaves; ++w) base += (w < wave) ? sh.wave_tot[w] : 0u;
-  return base + incl - v;
+  for (int c = 0; c < 4; ++c) {
+    if (above_me < M && M <= above_me + b[c]) found = true, bin_pos = c, above = above_me;
+    above_me += b[c];
+  }
+  return found;
+}
+
+// One wave scans a histogram of 256 bins (top bin first, four per lane) for the bin of the
+// M-th key from the top, `above` keys being above the whole histogram.  Returns the bin's
+// position from the top, updates `above` and sets `in_bin` to that bin's count; wave-uniform
+// results.
+__device__ __forceinline__ int topk_scan_256(const int* hist_top_first, int lane, int M, int& above, int& in_bin) {
+  const int4 v = *reinterpret_cast<const int4*>(hist_top_first + 4 * lane);
+  const int b[4] = {v.x, v.y, v.z, v.w};
+  const int tot = b[0] + b[1] + b[2] + b[3];
+  const int incl = (int)wave_scan_dpp((uint32_t)tot);
+  int pos = 0, mine_above = 0;
+  const bool found = topk_find_in_four(b, above + incl - tot, M, pos, mine_above);
+  const int mine_count = pos == 0 ? b[0] : pos == 1 ? b[1] : pos == 2 ? b[2] : b[3];
+  const unsigned long long who = __ballot(found);
+  // (no lane finds it only if the histogram does not belong to these scores, e.g. a
+  // workspace that was never initialised: any in-range answer will do then)
+  const int src = who ? (int)__builtin_ctzll(who) : 0;
+  above = __builtin_amdgcn_readlane(mine_above, src);
+  in_bin = __builtin_amdgcn_readlane(mine_count, src);
+  return __builtin_amdgcn_readlane(4 * lane + pos, src);
+}
+
+constexpr int kTopkLevelShift[kTopkLevels] = {12, 4, 0};
+constexpr int kTopkLevelBits[kTopkLevels] = {8, 8, 4};
+
+// The keys of a source that agree with `prefix` above level LEVEL's bits are counted into
+// that level's histogram.  `for_each_key(f)` calls f(key, valid) for every key of the
+// source, the same number of times on all lanes of a wave.  AGGREGATE: expect many equal
+// keys (a wave whose hits all fall into one bin adds them with one operation).
+template <int LEVEL, bool AGGREGATE, class Source>
+__device__ __forceinline__ void topk_level_count(uint32_t prefix, TopkShared& sh, Source&& for_each_key) {
+  constexpr int shift = kTopkLevelShift[LEVEL], bits = kTopkLevelBits[LEVEL], nbins = 1 << bits;
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint32_t hi = prefix >> (shift + bits);
+  for_each_key([&](uint32_t key, bool valid) __attribute__((always_inline)) {
+    const bool hit = valid && (key >> (shift + bits)) == hi;
+    const int slot = kTopkLevelBins - 1 - (int)((key >> shift) & (uint32_t)(nbins - 1));  // top bin first
+    if constexpr (!AGGREGATE) {
+      if (hit) atomicAdd(&sh.sub[LEVEL][slot], 1);
+      return;
+    }
+    const unsigned long long hits = __ballot(hit);
+    if (hits != 0ull) {  // uniform
+      // many equal scores would pile onto one counter: if every hit of the wave is in
+      // the same bin, one lane adds them all
+      const int first_hit = __builtin_ctzll(hits);
+      const int slot0 = __builtin_amdgcn_readlane(slot, first_hit);
+      if (__ballot(hit && slot == slot0) == hits) {
+        if (lane == first_hit) atomicAdd(&sh.sub[LEVEL][slot0], __popcll(hits));
+      } else if (hit) {
+        atomicAdd(&sh.sub[LEVEL][slot], 1);
+      }
+    }
+  });
+}
+
+// The scanning half of a level, by one wave: extends `prefix` by the level's bits of the
+// M-th key and `above` by the keys of higher bins; returns the number of keys in the bin found.
+template <int LEVEL>
+__device__ __forceinline__ int topk_level_scan(uint32_t& prefix, int& above, int M, TopkShared& sh) {
+  const int lane = threadIdx.x & (kWave - 1);
+  int in_bin;
+  const int pos = topk_scan_256(sh.sub[LEVEL], lane, M, above, in_bin);
+  prefix |= (uint32_t)((kTopkLevelBins - 1 - pos) & ((1 << kTopkLevelBits[LEVEL]) - 1)) << kTopkLevelShift[LEVEL];
+  return in_bin;
+}
+
+// A level run by the whole workgroup over a source that is spread over all waves: two barriers.
+template <int LEVEL, class Source>
+__device__ __forceinline__ void topk_level_block(uint32_t& prefix, int& above, int M, TopkShared& sh,
+                                                 Source&& for_each_key) {
+  topk_level_count<LEVEL, true>(prefix, sh, for_each_key);
+  lds_barrier();
+  if (threadIdx.x < kWave) {
+    topk_level_scan<LEVEL>(prefix, above, M, sh);
+    if (threadIdx.x == 0) sh.sel_key = prefix, sh.sel_above = above;
+  }
+  lds_barrier();
+  prefix = sh.sel_key;
+  above = sh.sel_above;
 }
 
 // All kTopkThreads lanes of the workgroup must call this with the same arguments.
 // g: NG scores (16-byte aligned if NG is a multiple of 4); out: M indices;
-// 1 <= M <= NG <= kTopkThreads * kTopkMaxPerLane.
+// 1 <= M <= NG <= kTopkThreads * SLOTS.
 // hist_global: nullptr => the histogram of the top 12 key bits is built here, in LDS;
-// otherwise it points at the problem's kTopkBins counters in global memory, completed
-// by an earlier kernel, and they are reset to zero on the way.
+// otherwise it points at the problem's kTopkBins counters in global memory (bin b at
+// index b), completed by an earlier kernel, and they are reset to zero on the way.
+template <int SLOTS>
 __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__ out, int NG, int M,
                                            int* hist_global, TopkShared& sh) {
+  static_assert(SLOTS % kTopkChunk == 0 && SLOTS <= kTopkMaxPerLane, "slots come in whole chunks");
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   // the problem's histogram, if it was accumulated elsewhere: requested first so that
-  // its latency overlaps the loads of the scores
-  int mine[kTopkBinsPerLane];  // bins 4095-4*tid downwards
-  if (hist_global) {
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c)
-      mine[c] = hist_global[kTopkBins - 1 - (tid * kTopkBinsPerLane + c)];
-  }
+  // its latency overlaps the loads of the scores.  A lane takes bins 4095-4*tid downwards.
+  int4 mine_raw = make_int4(0, 0, 0, 0);
+  int* const mine_global = hist_global ? hist_global + (kTopkBins - kTopkBinsPerLane * (tid + 1)) : nullptr;
+  if (hist_global) mine_raw = *reinterpret_cast<const int4*>(mine_global);
+
   // A lane owns a contiguous slice of kpt scores (what the ordered compaction needs).
   // With NG a multiple of four the slice is a whole number of 16-byte pieces and is
   // fetched as such: a wave then touches a few cache lines per load instead of 64.
@@ -101,18 +223,19 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
   int kpt = (NG + kTopkThreads - 1) / kTopkThreads;  // scores per lane
   if (vec) kpt = (kpt + 3) & ~3;
   const int first = tid * kpt;
+  const int n_real = max(0, min(kpt, NG - first));  // slots of this lane that hold a score
 
   // Slice of this lane, as keys, fetched in chunks of kTopkChunk slots whose loads are
   // all in flight together (addresses clamped, so no lane ever branches around a load).
-  // Slots beyond the slice (and beyond NG) hold key 0, which is below the key of every
-  // finite score.
-  uint32_t key[kTopkMaxPerLane];
+  // Slots beyond the slice (and beyond NG) hold key 0: below every score's key, and in a
+  // bin of the histogram that stays empty, so no later step has to tell them apart.
+  uint32_t key[SLOTS];
   {
     // every chunk's loads are requested before the first value is looked at, so a long
     // slice still costs one memory latency
-    float x[kTopkMaxPerLane];
+    float x[SLOTS];
 #pragma unroll
-    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
+    for (int c0 = 0; c0 < SLOTS; c0 += kTopkChunk) {
       if (c0 < kpt && vec) {  // uniform
 #pragma unroll
         for (int j = c0; j < c0 + kTopkChunk; j += 4) {
@@ -130,161 +253,174 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     // (pins every request above the first use: without it the compiler pairs each chunk's
     // loads with its conversions and waits chunk by chunk)
 #pragma unroll
-    for (int j = 0; j < kTopkMaxPerLane; ++j) asm volatile("" : "+v"(x[j]));
+    for (int j = 0; j < SLOTS; ++j) asm volatile("" : "+v"(x[j]));
 #pragma unroll
-    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
+    for (int c0 = 0; c0 < SLOTS; c0 += kTopkChunk) {
+      if (c0 < kpt) {  // uniform
 #pragma unroll
-      for (int j = c0; j < c0 + kTopkChunk; ++j)
-        key[j] = (c0 < kpt && j < kpt && first + j < NG) ? score_key(x[j]) : 0u;
+        for (int j = c0; j < c0 + kTopkChunk; ++j) key[j] = j < n_real ? score_key(x[j]) : 0u;
+      } else {
+#pragma unroll
+        for (int j = c0; j < c0 + kTopkChunk; ++j) key[j] = 0u;
+      }
     }
   }
+  // every key of this lane's slice, slot by slot (skipping the unused chunks uniformly)
+  auto slice_keys = [&](auto&& f) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c0 = 0; c0 < SLOTS; c0 += kTopkChunk) {
+      if (c0 < kpt) {  // uniform
+#pragma unroll
+        for (int j = c0; j < c0 + kTopkChunk; ++j) f(key[j], j);
+      }
+    }
+  };
 
   KVS_TOPK_TRACE(1);
+  // ---- 1. histogram of the top 12 bits, and the bin of the M-th key -------------------------
+  for (int i = tid; i < kTopkLevels * kTopkLevelBins; i += kTopkThreads) (&sh.sub[0][0])[i] = 0;
+  if (tid == 0) sh.n_listed = 0;  // (both ordered before their use by the barrier of this step)
+  int mine[kTopkBinsPerLane];     // bins 4095-4*tid downwards
   if (hist_global) {
-    // keep the histogram loads where they were written (ahead of the score loads) so that
-    // both latencies overlap instead of the compiler sinking them to their first use
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c) asm volatile("" : "+v"(mine[c]));
-  }
-  // ---- 1. histogram of the top 12 bits ------------------------------------------------
-  if (tid < kTopkLevels * 256) (&sh.sub[0][0])[tid] = 0;  // (ordered before their use by the barriers of step 1)
-  if (!hist_global) {
+    // (keeps the histogram load where it was written, ahead of the score loads, instead of
+    // the compiler sinking it to its first use)
+    asm volatile("" : "+v"(mine_raw.x), "+v"(mine_raw.y), "+v"(mine_raw.z), "+v"(mine_raw.w));
+    mine[0] = mine_raw.w, mine[1] = mine_raw.z, mine[2] = mine_raw.y, mine[3] = mine_raw.x;
+    *reinterpret_cast<int4*>(&sh.hist[kTopkBinsPerLane * tid]) = make_int4(mine[0], mine[1], mine[2], mine[3]);
+  } else {
     for (int i = tid; i < kTopkBins; i += kTopkThreads) sh.hist[i] = 0;
     lds_barrier();
-#pragma unroll
-    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-      if (c0 < kpt) {  // uniform
-#pragma unroll
-        for (int j = c0; j < c0 + kTopkChunk; ++j)
-          if (j < kpt && first + j < NG) atomicAdd(&sh.hist[key[j] >> kTopkLowBits], 1);
-      }
-    }
+    slice_keys([&](uint32_t k, int j) __attribute__((always_inline)) {
+      if (j < n_real) atomicAdd(&sh.hist[kTopkBins - 1 - (int)(k >> kTopkLowBits)], 1);
+    });
     lds_barrier();
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c)
-      mine[c] = sh.hist[kTopkBins - 1 - (tid * kTopkBinsPerLane + c)];
+    const int4 v = *reinterpret_cast<const int4*>(&sh.hist[kTopkBinsPerLane * tid]);
+    mine[0] = v.x, mine[1] = v.y, mine[2] = v.z, mine[3] = v.w;
   }
   KVS_TOPK_TRACE(2);
+  uint32_t prefix;
+  int above;  // keys in bins above the one that holds the M-th key
   {
-    uint32_t tot = 0;
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c) tot += (uint32_t)mine[c];
-    int above_me = (int)block_exclusive_scan(tot, sh);  // keys in bins above my first bin
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c) {
-      if (above_me < M && M <= above_me + mine[c]) {
-        sh.sel_bin = kTopkBins - 1 - (tid * kTopkBinsPerLane + c);
-        sh.sel_above = above_me;
-      }
-      above_me += mine[c];
-    }
+    const uint32_t tot = (uint32_t)(mine[0] + mine[1] + mine[2] + mine[3]);
+    const uint32_t incl = wave_scan_dpp(tot);
+    if (lane == kWave - 1) sh.wave_tot[0][wave] = incl;
+    lds_barrier();
+    // every wave by itself: which wave's 256 bins hold the M-th key, then which of those bins
+    const int w = lane & (kTopkWaves - 1);
+    const int t_w = (int)sh.wave_tot[0][w];
+    const int upto_w = row_scan_dpp(t_w);  // keys in the bins of waves 0..w
+    const unsigned long long reached = __ballot(upto_w >= M) & ((1ull << kTopkWaves) - 1ull);
+    const int w_sel = reached ? (int)__builtin_ctzll(reached) : kTopkWaves - 1;
+    above = __builtin_amdgcn_readlane(upto_w - t_w, w_sel);
+    int in_bin;
+    const int pos = topk_scan_256(&sh.hist[kTopkBinsPerWave * w_sel], lane, M, above, in_bin);
+    prefix = (uint32_t)(kTopkBins - 1 - (kTopkBinsPerWave * w_sel + pos)) << kTopkLowBits;
   }
-  lds_barrier();
-  const uint32_t bin = (uint32_t)sh.sel_bin;
-  uint32_t prefix = bin << kTopkLowBits;
-  int above = sh.sel_above;  // keys in higher bins; the M-th key is in `bin`
+  const uint32_t bin = prefix >> kTopkLowBits;
 
   KVS_TOPK_TRACE(3);
-  // ---- 2. settle the low 20 bits: three more histogram levels (8, 8 and 4 bits) ---------------
-  // Only the keys that agree with the prefix found so far take part - a few per cent after
-  // the first level, a handful after the second - so the LDS atomics are almost free of
-  // contention; wave 0 scans the (at most 256) bins of a level from the top with one DPP
-  // prefix sum.  Two barriers per level, nothing to gather, no limit on how many keys tie.
+  // ---- 2. settle the low 20 bits ---------------------------------------------------------
+  // The keys of the bin go into a list in LDS (in any order: only their values matter
+  // here): a lane counts its keys of the bin, a prefix sum over the wave and one atomic
+  // per wave give it its place in the list.
+  {
+    uint32_t n_mine = 0;
+    slice_keys([&](uint32_t k, int) __attribute__((always_inline)) {
+      n_mine += (k >> kTopkLowBits) == bin ? 1u : 0u;
+    });
+    const uint32_t incl = wave_scan_dpp(n_mine);
+    int wave_first = 0;
+    if (lane == kWave - 1 && incl != 0u) wave_first = atomicAdd(&sh.n_listed, (int)incl);
+    int at = __builtin_amdgcn_readlane(wave_first, kWave - 1) + (int)(incl - n_mine);
+    slice_keys([&](uint32_t k, int) __attribute__((always_inline)) {
+      if ((k >> kTopkLowBits) == bin) {
+        if (at < kTopkListCap) sh.list[at] = k;
+        ++at;
+      }
+    });
+  }
+  lds_barrier();
+  KVS_TOPK_TRACE(4);
+  const int n_listed = __builtin_amdgcn_readfirstlane(sh.n_listed);
+  if (n_listed <= kTopkListCap) {  // uniform
+    if (__builtin_amdgcn_readfirstlane(wave) == 0) {
+      // One wave takes the list into registers and runs the levels by itself: its LDS
+      // operations execute in order, so the counts of a level are complete when the same
+      // wave reads them back, and no barrier is needed between the levels.
+      uint32_t lk[kTopkListPerLane];
 #pragma unroll
-  for (int level = 0; level < kTopkLevels; ++level) {
-    constexpr int kShift[kTopkLevels] = {12, 4, 0};
-    constexpr int kBits[kTopkLevels] = {8, 8, 4};
-    const int shift = kShift[level], bits = kBits[level], nbins = 1 << bits;
-    const uint32_t hi = prefix >> (shift + bits);
+      for (int c = 0; c < kTopkListPerLane; ++c)
+        lk[c] = sh.list[min(c * kWave + lane, kTopkListCap - 1)];
+      auto listed_keys = [&](auto&& f) __attribute__((always_inline)) {
 #pragma unroll
-    for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-      if (c0 < kpt) {  // uniform
-#pragma unroll
-        for (int j = c0; j < c0 + kTopkChunk; ++j) {
-          const bool real = (j < kpt) && (first + j < NG);
-          const bool hit = real && (key[j] >> (shift + bits)) == hi;
-          const int sub_bin = (int)((key[j] >> shift) & (uint32_t)(nbins - 1));
-          const unsigned long long hits = __ballot(hit);
-          if (hits != 0ull) {  // uniform
-            // many equal scores would pile onto one counter: if every hit of the wave is in
-            // the same bin, one lane adds them all
-            const int first_hit = __builtin_ctzll(hits);
-            const int bin0 = __builtin_amdgcn_readlane(sub_bin, first_hit);
-            if (__ballot(hit && sub_bin == bin0) == hits) {
-              if (lane == first_hit) atomicAdd(&sh.sub[level][bin0], __popcll(hits));
-            } else if (hit) {
-              atomicAdd(&sh.sub[level][sub_bin], 1);
-            }
-          }
+        for (int c = 0; c < kTopkListPerLane; ++c)
+          if (c * kWave < n_listed) f(lk[c], c * kWave + lane < n_listed);  // uniform
+      };
+      // As soon as the bin found holds a single key, that key is T.
+      int settled = kTopkLevelShift[0];  // bits of `prefix` below this one are still open
+      topk_level_count<0, false>(prefix, sh, listed_keys);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      int in_bin = topk_level_scan<0>(prefix, above, M, sh);
+      if (in_bin != 1) {  // uniform
+        settled = kTopkLevelShift[1];
+        topk_level_count<1, false>(prefix, sh, listed_keys);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        in_bin = topk_level_scan<1>(prefix, above, M, sh);
+        if (in_bin != 1) {  // uniform
+          settled = kTopkLevelShift[2];
+          topk_level_count<2, false>(prefix, sh, listed_keys);
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          topk_level_scan<2>(prefix, above, M, sh);
         }
       }
+      if (settled != 0) {  // uniform
+        const uint32_t want = prefix >> settled;
+        listed_keys([&](uint32_t k, bool valid) __attribute__((always_inline)) {
+          const unsigned long long is = __ballot(valid && (k >> settled) == want);
+          if (is != 0ull) prefix = (uint32_t)__builtin_amdgcn_readlane((int)k, (int)__builtin_ctzll(is));
+        });
+      }
+      if (lane == 0) sh.sel_key = prefix, sh.sel_above = above;
     }
     lds_barrier();
-    if (wave == 0) {
-      int cnt[4];  // bins nbins-1-4*lane downwards
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int bin_c = nbins - 1 - (lane * 4 + c);
-        cnt[c] = bin_c >= 0 ? sh.sub[level][bin_c] : 0;
-      }
-      const uint32_t tot = (uint32_t)(cnt[0] + cnt[1] + cnt[2] + cnt[3]);
-      int above_me = above + (int)(wave_scan_dpp(tot) - tot);  // keys above my first bin
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if (above_me < M && M <= above_me + cnt[c]) {
-          sh.sel_bin = nbins - 1 - (lane * 4 + c);
-          sh.sel_above = above_me;
-        }
-        above_me += cnt[c];
-      }
-    }
-    lds_barrier();
-    prefix |= (uint32_t)sh.sel_bin << shift;
+    prefix = sh.sel_key;
     above = sh.sel_above;
+  } else {
+    auto all_keys = [&](auto&& f) __attribute__((always_inline)) {
+      slice_keys([&](uint32_t k, int j) __attribute__((always_inline)) { f(k, j < n_real); });
+    };
+    topk_level_block<0>(prefix, above, M, sh, all_keys);
+    topk_level_block<1>(prefix, above, M, sh, all_keys);
+    topk_level_block<2>(prefix, above, M, sh, all_keys);
   }
   KVS_TOPK_TRACE(5);
   // Selected: keys > T, plus the first `need` keys equal to T in index order.
-  const uint32_t T = prefix;   // the M-th largest key
+  // (T below the smallest key of a score can only come from a histogram that does not
+  // belong to these scores, e.g. a workspace that was never initialised: the unused slots
+  // must stay unselected even then)
+  const uint32_t T = max(prefix, kTopkMinKey);  // the M-th largest key
   const int need = M - above;  // `above` keys are greater than T
 
   // ---- 3. ordered compaction -------------------------------------------------------------
   uint32_t packed = 0;  // low half: keys > T, high half: keys == T
-#pragma unroll
-  for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-    if (c0 < kpt) {  // uniform
-#pragma unroll
-      for (int j = c0; j < c0 + kTopkChunk; ++j) {
-        const bool real = (j < kpt) && (first + j < NG);
-        packed += (real && key[j] > T) ? 1u : 0u;
-        packed += (real && key[j] == T) ? 0x10000u : 0u;
-      }
-    }
-  }
-  const uint32_t excl = block_exclusive_scan(packed, sh);
+  slice_keys([&](uint32_t k, int) __attribute__((always_inline)) {
+    packed += k > T ? 1u : 0u;
+    packed += k == T ? 0x10000u : 0u;
+  });
+  const uint32_t excl = block_exclusive_scan(packed, sh.wave_tot[1]);
   KVS_TOPK_TRACE(6);
   int gt_before = (int)(excl & 0xFFFFu);
   int eq_before = (int)(excl >> 16);
-#pragma unroll
-  for (int c0 = 0; c0 < kTopkMaxPerLane; c0 += kTopkChunk) {
-    if (c0 < kpt) {  // uniform
-#pragma unroll
-      for (int j = c0; j < c0 + kTopkChunk; ++j) {
-        if (j < kpt && first + j < NG) {
-          const bool gt = key[j] > T, eq = key[j] == T;
-          // (the bound only matters if the caller handed in a histogram that does not
-          // belong to these scores, e.g. a workspace that was never initialised)
-          const int pos = gt_before + min(eq_before, need);
-          if ((gt || (eq && eq_before < need)) && pos < M) out[pos] = first + j;
-          gt_before += gt ? 1 : 0;
-          eq_before += eq ? 1 : 0;
-        }
-      }
-    }
-  }
-  if (hist_global) {
-#pragma unroll
-    for (int c = 0; c < kTopkBinsPerLane; ++c)  // leave the counters zero for the next call
-      if (mine[c]) hist_global[kTopkBins - 1 - (tid * kTopkBinsPerLane + c)] = 0;
+  slice_keys([&](uint32_t k, int j) __attribute__((always_inline)) {
+    const bool gt = k > T, eq = k == T;
+    // (the bound only matters with a histogram that does not belong to these scores)
+    const int pos = gt_before + min(eq_before, need);
+    if ((gt || (eq && eq_before < need)) && pos < M) out[pos] = first + j;
+    gt_before += gt ? 1 : 0;
+    eq_before += eq ? 1 : 0;
+  });
+  if (hist_global) {  // leave the counters zero for the next call
+    if ((mine[0] | mine[1] | mine[2] | mine[3]) != 0) *reinterpret_cast<int4*>(mine_global) = make_int4(0, 0, 0, 0);
   }
 }
 
