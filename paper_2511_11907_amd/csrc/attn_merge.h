@@ -5,6 +5,8 @@
 // log2 units).
 #pragma once
 
+#include <type_traits>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -30,6 +32,7 @@ namespace kvs {
 constexpr int kAttnThreads = kAttnWgThreads;
 constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kAttnMaxSplits = kAttnMaxSplitsPerProblem;
+constexpr int kAttnMergeRound = 32;  // splits whose partial results the final merge requests together
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite on purpose)
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -68,7 +71,6 @@ struct AttnWaveStates {
   static __device__ __forceinline__ int pos(int h, int d) { return d * QPK + h + (d / 32) * kPad; }
   float m[kAttnWaves][QPK];
   float l[kAttnWaves][QPK];
-  float w[kAttnWaves][QPK];  // scratch of the merge
   float o[kAttnWaves][kWords];
 };
 
@@ -83,32 +85,42 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   auto& s_m = ws.m;
   auto& s_l = ws.l;
-  auto& s_w = ws.w;
   auto& s_o = ws.o;
   lds_barrier();
-  // per head: workgroup max, weights, sum of l
+  // Every lane merges the waves' states for its own (head, d) elements.  The waves' weights
+  // exp2(m_wave - m) are recomputed by every lane (a few instructions) rather than computed
+  // once and handed on through LDS, which would cost a barrier.
   float* ml = part_ml + ((size_t)p * n_splits + split) * QPK * 2;
-  if (tid < QPK) {
-    float mt = kNegBig;
-    for (int s = 0; s < kAttnWaves; ++s) mt = fmaxf(mt, s_m[s][tid]);
-    float lt = 0.f;
-    for (int s = 0; s < kAttnWaves; ++s) {
-      const float w = __builtin_amdgcn_exp2f(s_m[s][tid] - mt);
-      s_w[s][tid] = w;
-      lt += w * s_l[s][tid];
-    }
-    publish_store(&ml[tid * 2 + 0], mt);
-    publish_store(&ml[tid * 2 + 1], lt);
-  }
-  lds_barrier();
   float* po = part_o + ((size_t)p * n_splits + split) * QPK * D;
   for (int i = tid; i < QPK * D; i += kAttnThreads) {  // i = d * QPK + h
     const int h = i % QPK, dd = i / QPK;
     const int at = AttnWaveStates<D, QPK>::pos(h, dd);
-    float acc = 0.f;
-    for (int s = 0; s < kAttnWaves; ++s) acc = fmaf(s_w[s][h], s_o[s][at], acc);
-    publish_store(&po[i], acc);
+    float m_w[kAttnWaves], l_w[kAttnWaves], o_w[kAttnWaves];
+#pragma unroll
+    for (int s = 0; s < kAttnWaves; ++s) m_w[s] = s_m[s][h], l_w[s] = s_l[s][h], o_w[s] = s_o[s][at];
+    float mt = kNegBig;
+#pragma unroll
+    for (int s = 0; s < kAttnWaves; ++s) mt = fmaxf(mt, m_w[s]);
+    float lt = 0.f, acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < kAttnWaves; ++s) {
+      const float w = __builtin_amdgcn_exp2f(m_w[s] - mt);
+      lt += w * l_w[s];
+      acc = fmaf(w, o_w[s], acc);
+    }
+    if (n_splits == 1) {  // uniform: the problem was not split, this is its result
+      const float r = acc / lt;
+      if constexpr (E::kBytes == 2) op[h * D + dd] = float_to_bf16_bits(r);
+      else op[h * D + dd] = r;
+    } else {
+      publish_store(&po[i], acc);
+      if (dd == 0) {
+        publish_store(&ml[h * 2 + 0], mt);
+        publish_store(&ml[h * 2 + 1], lt);
+      }
+    }
   }
+  if (n_splits == 1) return;  // uniform
 
   // ---- the last workgroup of the problem merges the splits ------------------------
   __shared__ int s_last;
@@ -158,21 +170,30 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   for (int i = tid; i < QPK * D; i += kAttnThreads) {  // i = d * QPK + h
     const int h = i % QPK, dd = i / QPK;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    // kBatch splits at a time, all their loads requested before the first is used: these
-    // loads go past the caches, and four at a time (the first version) meant one full
-    // memory latency per four splits - 8 in a row at 32 splits per problem
-    constexpr int kBatch = 16;
-    for (int s0 = 0; s0 < n_splits; s0 += kBatch) {
-      float v[kBatch];
+    // The partial results of many splits are requested together before the first is used:
+    // these loads go past the caches, so every round of requests costs a full memory
+    // latency.  Whole rounds of kAttnMergeRound splits, then one round for the rest, sized
+    // to the next power of two (indices clamped, surplus weights zero).
+    auto take = [&](auto round_size, int s0) __attribute__((always_inline)) {
+      constexpr int kRound = decltype(round_size)::value;
+      float v[kRound];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j)
+      for (int j = 0; j < kRound; ++j)
         v[j] = load_published(&ppo[(size_t)min(s0 + j, n_splits - 1) * QPK * D + i]);
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
+      for (int j = 0; j < kRound; ++j) {
         const float w = (s0 + j < n_splits) ? s_cw[min(s0 + j, n_splits - 1)][h] : 0.f;
         acc[j & 3] = fmaf(w, v[j], acc[j & 3]);
       }
-    }
+    };
+    int s0 = 0;
+    for (; s0 + kAttnMergeRound <= n_splits; s0 += kAttnMergeRound)
+      take(std::integral_constant<int, kAttnMergeRound>{}, s0);
+    const int rest = n_splits - s0;  // uniform
+    if (rest > 16) take(std::integral_constant<int, 32>{}, s0);
+    else if (rest > 8) take(std::integral_constant<int, 16>{}, s0);
+    else if (rest > 4) take(std::integral_constant<int, 8>{}, s0);
+    else if (rest > 0) take(std::integral_constant<int, 4>{}, s0);
     const float r = ((acc[0] + acc[1]) + (acc[2] + acc[3])) / s_cl[h];
     if constexpr (E::kBytes == 2) op[h * D + dd] = float_to_bf16_bits(r);
     else op[h * D + dd] = r;

@@ -149,6 +149,23 @@ def test_one_problem_cut_into_the_maximum_number_of_splits():
     _say(cfg2.name, H.run_and_compare(cfg2, check_meta=False))
 
 
+def test_more_problems_than_workgroups_one_split_each():
+    """More (sequence, KV head) problems than the attention launch has workgroups to hand
+    out: every problem is one split of several workgroup steps and writes its result
+    itself, without partial results or an arrival counter.  Also split counts that make
+    the final merge take its partial results in rounds of 4, 8, 16 and 32, the last with a
+    remainder."""
+    cfg = _cfg("320_problems_matrix_core", "bf16", 32, 8, 128, 32, 4, 512, 128, B=40)
+    _say(cfg.name, H.run_and_compare(cfg, check_meta=False))
+    cfg2 = _cfg("576_problems_valu_f32", "f32", 16, 8, 64, 16, 4, 256, 96, B=72)
+    _say(cfg2.name, H.run_and_compare(cfg2, check_meta=False))
+    for name, B, Hk, NG, M in (("3_splits", 11, 8, 1024, 96), ("6_splits", 5, 8, 1024, 192),
+                               ("12_splits", 11, 2, 2048, 400), ("20_splits", 13, 1, 2048, 700),
+                               ("39_splits", 3, 2, 4096, 1400)):
+        c = _cfg(name, "bf16", 4 * Hk, Hk, 128, 32, 4, NG, M, B=B)
+        _say(c.name, H.run_and_compare(c, check_meta=False))
+
+
 # ---- the paper's operating point at full context length, oracle on sampled problems ------------
 def test_qwen3_14b_layer_32k_g12_full_size_sampled():
     """40 query / 8 KV heads, 32 760 tokens, G = 12, M = 33 (M*G = 396), batch 4."""
