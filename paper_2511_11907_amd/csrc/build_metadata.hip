@@ -99,6 +99,20 @@ __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
+// Exchanges between a wave's lanes for the stores (gfx950's lane-swap instructions, layouts
+// checked on the device): after swap_upper_lower_half(a, b) lanes 32..63 of a hold what
+// lanes 0..31 of b held and vice versa; after swap_odd_even_rows(a, b) the odd rows of 16
+// lanes of a hold what the even rows of b held (row 1 <- row 0, row 3 <- row 2) and vice
+// versa.
+__device__ __forceinline__ void swap_upper_lower_half(uint32_t& a, uint32_t& b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0], b = r[1];
+}
+__device__ __forceinline__ void swap_odd_even_rows(uint32_t& a, uint32_t& b) {
+  const auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+  a = r[0], b = r[1];
+}
+
 constexpr int kMfmaThreads = 256;
 constexpr int kMfmaWaves = kMfmaThreads / kWave;
 constexpr int kMfmaTokenBlocks = 2;                         // blocks of 16 tokens per wave
@@ -197,6 +211,41 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       const int row = row_of(tile, tb);
+      if constexpr (EM::kBytes == 2 && (MB == 2 || MB == 4)) {
+        if (cols == 16 * MB) {  // uniform: whole rank blocks, the usual case
+          // The four lanes of a token hold 8 bytes of each rank block; exchanged between
+          // them (rank block <-> lane group) every lane ends up with 16 or 32 consecutive
+          // bytes of the row, and one or two store instructions write whole rows.
+          uint32_t lo[MB], hi[MB];
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = acc[tb][mb][j] / meta_scale;
+            lo[mb] = float_to_bf16_bits(v[0]) | (uint32_t)float_to_bf16_bits(v[1]) << 16;
+            hi[mb] = float_to_bf16_bits(v[2]) | (uint32_t)float_to_bf16_bits(v[3]) << 16;
+          }
+          if constexpr (MB == 4) {
+            swap_upper_lower_half(lo[0], lo[2]), swap_upper_lower_half(lo[1], lo[3]);
+            swap_upper_lower_half(hi[0], hi[2]), swap_upper_lower_half(hi[1], hi[3]);
+            swap_odd_even_rows(lo[0], lo[1]), swap_odd_even_rows(lo[2], lo[3]);
+            swap_odd_even_rows(hi[0], hi[1]), swap_odd_even_rows(hi[2], hi[3]);
+            // lane group kq now holds ranks kq*16 .. kq*16 + 15 of its token
+            if (row < row_end) {
+              uint4* o = reinterpret_cast<uint4*>(Op + (size_t)row * r + col0 + kq * 16);
+              o[0] = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+              o[1] = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+            }
+          } else {
+            swap_odd_even_rows(lo[0], lo[1]), swap_odd_even_rows(hi[0], hi[1]);
+            // lane group kq now holds ranks (kq & 1) * 16 + (kq & 2) * 4 .. + 7 of its token
+            if (row < row_end)
+              *reinterpret_cast<uint4*>(Op + (size_t)row * r + col0 + (kq & 1) * 16 + (kq & 2) * 4) =
+                  make_uint4(lo[0], hi[0], lo[1], hi[1]);
+          }
+          continue;
+        }
+      }
       if (row < row_end) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
