@@ -246,6 +246,31 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
           continue;
         }
       }
+      if constexpr (EM::kBytes == 1 && (MB == 2 || MB == 4)) {
+        if (cols == 16 * MB) {  // uniform; the same exchange with four one-byte values per rank block
+          uint32_t b4[MB];
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = acc[tb][mb][j] / meta_scale;
+            b4[mb] = float_to_fp8_e4m3(v[0]) | (uint32_t)float_to_fp8_e4m3(v[1]) << 8 |
+                     (uint32_t)float_to_fp8_e4m3(v[2]) << 16 | (uint32_t)float_to_fp8_e4m3(v[3]) << 24;
+          }
+          if constexpr (MB == 4) {
+            swap_upper_lower_half(b4[0], b4[2]), swap_upper_lower_half(b4[1], b4[3]);
+            swap_odd_even_rows(b4[0], b4[1]), swap_odd_even_rows(b4[2], b4[3]);
+            if (row < row_end)
+              *reinterpret_cast<uint4*>(Op + (size_t)row * r + col0 + kq * 16) = make_uint4(b4[0], b4[1], b4[2], b4[3]);
+          } else {
+            swap_odd_even_rows(b4[0], b4[1]);
+            if (row < row_end)
+              *reinterpret_cast<uint2*>(Op + (size_t)row * r + col0 + (kq & 1) * 16 + (kq & 2) * 4) =
+                  make_uint2(b4[0], b4[1]);
+          }
+          continue;
+        }
+      }
       if (row < row_end) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
