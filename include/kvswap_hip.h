@@ -58,7 +58,11 @@
  * attention kernel hands the final merge to the workgroup that finishes last)
  * that must be zero when a call starts: call kvs_workspace_init once after
  * allocating (or zero-fill the buffer yourself); every call then leaves the
- * counters zero for the next one.
+ * counters zero for the next one, PROVIDED all of its launches ran: after any call
+ * that returned KVS_ERR_DEVICE (a launch failed part-way through a call) the counters
+ * may be left non-zero, and the workspace must be prepared with kvs_workspace_init
+ * again before it is reused.  This counter area is the only thing the library keeps
+ * from one call to the next, and it keeps it in the caller's buffer.
  * The rest of the workspace is undefined on entry and on return.  Calls that
  * share a workspace must be ordered on one stream (they would race otherwise).
  * The layout of the counter area depends only on batch, n_kv_heads and head_mode:
@@ -174,10 +178,17 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
  * kvs_predict_scores writes group_scores [B,H_kv,N/G] (required here);
  * kvs_select_topk reads them and writes idx.  workspace may be NULL in both: the
  * selection then builds its own score histogram (joint mode: kvs_predict_scores
- * needs the workspace, KVS_ERR_WORKSPACE without).  If kvs_predict_scores is given a
- * workspace it also leaves the per-problem score histograms there, and the NEXT call
- * on that workspace must be kvs_select_topk with the same workspace and params (it
- * consumes the histograms and zeroes them again). */
+ * needs the workspace, KVS_ERR_WORKSPACE without).
+ * Contract of a non-NULL workspace: if kvs_predict_scores is given a workspace it also
+ * leaves the per-problem score histograms there, and the NEXT call on that workspace
+ * must be kvs_select_topk with the same workspace, params and group_scores (it consumes
+ * the histograms and zeroes them again).  Conversely, a workspace passed to
+ * kvs_select_topk is expected to hold the histograms of exactly these group_scores.
+ * The selection checks that a histogram counts N/G scores in all; one that does not
+ * (scores that came from elsewhere, or from kvs_predict_scores without a workspace)
+ * is ignored, the selection builds its own and is still exact, and the counters are
+ * zeroed all the same.  A histogram of the right total that belongs to other scores
+ * cannot be told apart and gives an unspecified (in-range, M-element) selection. */
 kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_lr,
                               const float* A, float* group_scores, void* workspace,
                               size_t workspace_bytes, void* stream);
@@ -203,7 +214,7 @@ kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const v
                                      void* out, void* workspace, size_t workspace_bytes,
                                      void* stream);
 
-/* Sec. 3.4.3 (KV cache manager): the same attention with the KV groups addressed
+/* Sec. 3.4.4 (KV cache manager): the same attention with the KV groups addressed
  * through a mapping table, as an operating system addresses pages.  K_pool, V_pool
  * [n_slots, G, d] (kv_dtype) are pools of group-sized slots shared by all problems;
  * slot_table [B, H_kv, N/G] int32 gives the slot that holds logical group j of

@@ -437,7 +437,7 @@ int oracle_dense_attn(const orc_params* p, const void* q, const void* K, const v
   return failed ? -2 : 0;
 }
 
-/* ---- mapping table (Sec. 3.4.3) and selection overlap (Sec. 3.4.2) --------- */
+/* ---- mapping table (Sec. 3.4.4) and selection overlap (Sec. 3.4.2) --------- */
 
 int oracle_sparse_attn_paged(const orc_params* p, const void* q, const void* K_pool,
                              const void* V_pool, const int32_t* slot_table, int32_t n_slots,

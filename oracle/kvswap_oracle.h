@@ -126,7 +126,7 @@ int oracle_sparse_attn_rb(const orc_params* p, const void* q, const void* K,
                           const void* rb_V, int32_t rb_len, int32_t rb_capacity,
                           double* out);
 
-/* The same through a mapping table (Sec. 3.4.3 "KV cache manager": attention addresses
+/* The same through a mapping table (Sec. 3.4.4 "KV cache manager": attention addresses
  * its KV groups logically, a table maps them to where they physically are).  K_pool and
  * V_pool are [n_slots, G, d]: slots of one group each, in any order and shared by all
  * problems; slot_table [B, H_kv, NG] gives the slot of logical group j of (b, kv head).

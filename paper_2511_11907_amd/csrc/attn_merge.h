@@ -40,7 +40,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 // compiled out of the modes below it, so the plain path pays nothing for them:
 //   kAttnPlain   selected groups are rows of this problem's contiguous cache
 //   kAttnRolling + the attended-token list continues into a rolling buffer (Sec. 3.4.1)
-//   kAttnPaged   + groups are addressed through a mapping table (Sec. 3.4.3): K and V are
+//   kAttnPaged   + groups are addressed through a mapping table (Sec. 3.4.4): K and V are
 //                  pools of group-sized slots shared by all problems, slot_table[p][j]
 //                  is the slot that holds logical group j of problem p
 constexpr int kAttnPlain = 0, kAttnRolling = 1, kAttnPaged = 2;
@@ -137,6 +137,7 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
   lds_barrier();
   KVS_ATTN_TRACE(5);
   if (!s_last) return;
+  consume_fence();
   const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
   for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
     // (m, l) of this lane's splits, all requested at once: one memory latency

@@ -209,9 +209,20 @@ __device__ __forceinline__ int load_published(const int* p) {
 // Every lane calls this after its last publish_store / device-scope atomic: all of
 // this lane's outstanding memory operations have completed, then a workgroup barrier.
 // After it, one lane may bump the arrival counter.
+// The wait and the barrier are hardware ordering; towards the compiler they are no memory
+// barriers for global memory, so a compiler-only fence on either side keeps it from moving
+// a publish_store below the wait or a later access above it (no instruction is emitted).
 __device__ __forceinline__ void publish_complete_and_barrier() {
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   lds_barrier();
 }
+
+// Placed between learning (from an arrival counter or a flag) that another workgroup's
+// values are published and the first load_published of them: keeps the compiler from
+// hoisting those loads above the point where the arrival is known (no instruction is
+// emitted; the hardware returns the loads of a wave in order).
+__device__ __forceinline__ void consume_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 
 }  // namespace kvs

@@ -105,7 +105,7 @@ hipError_t launch_attn_mfma(const kvs_params& p, const Plan& pl, const void* q, 
                        void* out, int* arrivals, const RollingBuffer& rb, const int32_t* slot_table,
                        hipStream_t st);
 // slot_table != nullptr: K and V are pools [n_slots, G, d] and slot_table [P, NG] maps the
-// logical groups of each problem to slots (Sec. 3.4.3).
+// logical groups of each problem to slots (Sec. 3.4.4).
 // common[s] = |idx_prev[s,:] ∩ idx_cur[s,:]| per selection set
 hipError_t launch_overlap(const kvs_params& p, const Plan& pl, const int32_t* idx_prev,
                           const int32_t* idx_cur, int32_t* common, hipStream_t st);

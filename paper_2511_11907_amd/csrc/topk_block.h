@@ -281,13 +281,8 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
   for (int i = tid; i < kTopkLevels * kTopkLevelBins; i += kTopkThreads) (&sh.sub[0][0])[i] = 0;
   if (tid == 0) sh.n_listed = 0;  // (both ordered before their use by the barrier of this step)
   int mine[kTopkBinsPerLane];     // bins 4095-4*tid downwards
-  if (hist_global) {
-    // (keeps the histogram load where it was written, ahead of the score loads, instead of
-    // the compiler sinking it to its first use)
-    asm volatile("" : "+v"(mine_raw.x), "+v"(mine_raw.y), "+v"(mine_raw.z), "+v"(mine_raw.w));
-    mine[0] = mine_raw.w, mine[1] = mine_raw.z, mine[2] = mine_raw.y, mine[3] = mine_raw.x;
-    *reinterpret_cast<int4*>(&sh.hist[kTopkBinsPerLane * tid]) = make_int4(mine[0], mine[1], mine[2], mine[3]);
-  } else {
+  // the histogram built here, in LDS, from the keys in registers (two barriers)
+  auto build_here = [&]() __attribute__((always_inline)) {
     for (int i = tid; i < kTopkBins; i += kTopkThreads) sh.hist[i] = 0;
     lds_barrier();
     slice_keys([&](uint32_t k, int j) __attribute__((always_inline)) {
@@ -296,18 +291,28 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     lds_barrier();
     const int4 v = *reinterpret_cast<const int4*>(&sh.hist[kTopkBinsPerLane * tid]);
     mine[0] = v.x, mine[1] = v.y, mine[2] = v.z, mine[3] = v.w;
+  };
+  if (hist_global) {
+    // (keeps the histogram load where it was written, ahead of the score loads, instead of
+    // the compiler sinking it to its first use)
+    asm volatile("" : "+v"(mine_raw.x), "+v"(mine_raw.y), "+v"(mine_raw.z), "+v"(mine_raw.w));
+    mine[0] = mine_raw.w, mine[1] = mine_raw.z, mine[2] = mine_raw.y, mine[3] = mine_raw.x;
+    *reinterpret_cast<int4*>(&sh.hist[kTopkBinsPerLane * tid]) = make_int4(mine[0], mine[1], mine[2], mine[3]);
+  } else {
+    build_here();
   }
   KVS_TOPK_TRACE(2);
   uint32_t prefix;
   int above;  // keys in bins above the one that holds the M-th key
-  {
+  // Every wave by itself, after one barrier: which wave's 256 bins hold the M-th key, then
+  // which of those bins.  Returns the number of keys the histogram holds in all.
+  auto locate = [&](uint32_t* wave_tot) __attribute__((always_inline)) {
     const uint32_t tot = (uint32_t)(mine[0] + mine[1] + mine[2] + mine[3]);
     const uint32_t incl = wave_scan_dpp(tot);
-    if (lane == kWave - 1) sh.wave_tot[0][wave] = incl;
+    if (lane == kWave - 1) wave_tot[wave] = incl;
     lds_barrier();
-    // every wave by itself: which wave's 256 bins hold the M-th key, then which of those bins
     const int w = lane & (kTopkWaves - 1);
-    const int t_w = (int)sh.wave_tot[0][w];
+    const int t_w = (int)wave_tot[w];
     const int upto_w = row_scan_dpp(t_w);  // keys in the bins of waves 0..w
     const unsigned long long reached = __ballot(upto_w >= M) & ((1ull << kTopkWaves) - 1ull);
     const int w_sel = reached ? (int)__builtin_ctzll(reached) : kTopkWaves - 1;
@@ -315,6 +320,19 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     int in_bin;
     const int pos = topk_scan_256(&sh.hist[kTopkBinsPerWave * w_sel], lane, M, above, in_bin);
     prefix = (uint32_t)(kTopkBins - 1 - (kTopkBinsPerWave * w_sel + pos)) << kTopkLowBits;
+    return __builtin_amdgcn_readlane(upto_w, kTopkWaves - 1);
+  };
+  const int counted = locate(sh.wave_tot[0]);
+  if (hist_global && counted != NG) {  // uniform
+    // The histogram handed in does not hold exactly these NG scores (it was never
+    // accumulated for them, or the counters were not zero before): it is ignored and the
+    // histogram is built here after all.  The barrier lets every wave finish reading the
+    // old histogram before it is cleared; the per-wave totals go to the second array
+    // because a wave may still be reading the first (the placement scan, which uses the
+    // second array again, comes after the barriers of step 2).
+    lds_barrier();
+    build_here();
+    locate(sh.wave_tot[1]);
   }
   const uint32_t bin = prefix >> kTopkLowBits;
 
@@ -420,7 +438,7 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     eq_before += eq ? 1 : 0;
   });
   if (hist_global) {  // leave the counters zero for the next call
-    if ((mine[0] | mine[1] | mine[2] | mine[3]) != 0) *reinterpret_cast<int4*>(mine_global) = make_int4(0, 0, 0, 0);
+    if ((mine_raw.x | mine_raw.y | mine_raw.z | mine_raw.w) != 0) *reinterpret_cast<int4*>(mine_global) = make_int4(0, 0, 0, 0);
   }
 }
 

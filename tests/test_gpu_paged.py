@@ -1,4 +1,4 @@
-"""GPU parity of attention through a mapping table (Sec. 3.4.3: KV groups addressed
+"""GPU parity of attention through a mapping table (Sec. 3.4.4: KV groups addressed
 logically, a table says in which physical slot each one is) and of the selection-overlap
 count (Sec. 3.4.2), against the CPU oracle, through the C-ABI binding."""
 import numpy as np

@@ -124,3 +124,67 @@ def test_infinities_and_mixed_signs():
     gs[:, RNG.choice(NG, 50, replace=False)] = -0.0
     for M in (1, 7, 8, 820, NG - 300, NG - 299, NG):
         _check(gs, M, f"infinities M={M}")
+
+
+def _select_with_workspace(gs: np.ndarray, M: int, ws, p):
+    P, NG = gs.shape
+    d_gs = torch.from_numpy(np.ascontiguousarray(gs)).to(H.DEV).view(P, 1, NG)
+    idx = torch.full((P, 1, M), -7, dtype=torch.int32, device=H.DEV)
+    kv.kvs_select_topk(p, d_gs, idx, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy().reshape(P, M)
+
+
+@pytest.mark.parametrize("NG,M", [(8192, 820), (16384, 2048), (1000, 77)])
+def test_workspace_whose_histogram_is_not_of_these_scores(NG, M):
+    """kvs_select_topk with a workspace whose histogram area does not belong to the scores:
+    all zero (the scores came from elsewhere, or from kvs_predict_scores called without a
+    workspace), and then holding another call's left-over counts.  The selection must notice
+    (the histogram does not count NG scores), build its own, be exact, and leave the counters
+    zero."""
+    P, G = 3, 4
+    p = kv.Params(P, 4, 1, 128, 32, NG * G, G, M, kv.KVS_BF16, kv.KVS_BF16)
+    gs = (RNG.standard_normal((P, NG)) * 20.0).astype(np.float32)
+    want = _by_definition(gs, M)
+    ws = H.workspace(p)
+    got = _select_with_workspace(gs, M, ws, p)
+    assert np.array_equal(got, want), "zeroed histogram"
+    # counters of a prediction that was never consumed: the histograms of other scores, twice
+    L_q = torch.randn((P, 4, 128), device=H.DEV).to(torch.bfloat16)
+    klr = torch.randn((P, 1, NG * G, 32), device=H.DEV).to(torch.bfloat16)
+    A = torch.randn((1, 128, 32), device=H.DEV)
+    other = torch.empty((P, 1, NG), dtype=torch.float32, device=H.DEV)
+    kv.kvs_predict_scores(p, L_q, klr, A, other, ws)
+    kv.kvs_predict_scores(p, L_q, klr, A, other, ws)
+    got = _select_with_workspace(gs, M, ws, p)
+    assert np.array_equal(got, want), "histogram holding 2 x NG foreign counts"
+    # ... and that call left the counters zero: the paired calls work again and are exact
+    kv.kvs_predict_scores(p, L_q, klr, A, other, ws)
+    idx = torch.empty((P, 1, M), dtype=torch.int32, device=H.DEV)
+    kv.kvs_select_topk(p, other, idx, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy().reshape(P, M), _by_definition(other.cpu().numpy().reshape(P, NG), M))
+
+
+def test_scores_predicted_without_a_workspace_then_selected_with_one():
+    """The pattern the header warns about: kvs_predict_scores(workspace = NULL) followed by
+    kvs_select_topk(workspace): must equal the oracle's selection."""
+    import oracle
+    from workloads import PRESETS, make_layer
+    cfg = PRESETS["c2"].replace(name="c2s", batch=2, ctx_len=4096, n_select=103)
+    L = make_layer(cfg)
+    sh = H.orc_shape(cfg)
+    klr = oracle.build_metadata(sh, L.K, L.A)
+    ref = oracle.predict_select(sh, L.q, klr, L.A)
+    p = H.kv_params(cfg)
+    ws = H.workspace(p)
+    gs = torch.empty(p.sets + (cfg.n_groups,), dtype=torch.float32, device=H.DEV)
+    idx = torch.full(p.sets + (cfg.n_select,), -1, dtype=torch.int32, device=H.DEV)
+    kv.kvs_predict_scores(p, H.to_dev(L.q), H.to_dev(klr), H.to_dev(L.A), gs, None)
+    kv.kvs_select_topk(p, gs, idx, ws)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    for b in range(cfg.batch):
+        for k in range(cfg.n_kv_heads):
+            if H.check_index_margin(idx_h[b, k], ref["gs"][b, k], ref["boundary"][b, k], f"b={b} k={k}"):
+                assert np.array_equal(idx_h[b, k], ref["idx"][b, k])

@@ -1,4 +1,4 @@
-"""Pins of the oracle's mapping-table attention (Sec. 3.4.3 "KV cache manager": KV groups
+"""Pins of the oracle's mapping-table attention (Sec. 3.4.4 "KV cache manager": KV groups
 are addressed logically, a table says where they physically are) and of the selection
 overlap count (Sec. 3.4.2: overlap ratio of consecutive steps), against things other
 than itself."""
