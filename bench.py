@@ -8,12 +8,16 @@ resident in HBM.  Steps rotate over several independent copies of the inputs so
 that the working set of consecutive steps exceeds the on-chip caches (the 32K,
 batch-1 working set alone would fit the 256 MB last-level cache).
 
-    python bench.py --gpus 1 --steps K --warmup W [--config c2] [--mode graph|eager]
+    python bench.py --gpus 1 --steps K --warmup W [--config c4] [--extra c1,c2,c3,c5] [--mode graph|eager]
 
-prints ONE JSON line: tokens/s (= batch / step latency) as `value`, the latency
-itself in `ms_per_step` / `us_per_layer`, a `roofline` object for the dominant
-kernel (algorithmic bytes / measured kernel time against 8 TB/s) and a
-`cpu_baseline` object (the fp64 CPU oracle timed on this machine's host cores).
+prints ONE JSON line.  The headline workload (default c4, the largest single-layer one:
+128K context, batch 4) gives tokens/s (= batch / step latency) as `value`, the latency
+itself in `ms_per_step` / `us_per_layer`, a `roofline` object for the dominant kernel
+(algorithmic bytes / measured kernel time against 8 TB/s) and a `cpu_baseline` object (the
+fp64 CPU oracle timed on this machine's host cores).  The other workloads follow under
+`other_workloads`, each with its own latency, roofline and cpu_baseline: c1 (4K, fp32:
+microseconds only), c2 and c3 (32K context, batch 1 and 8) and c5 (a whole 36-layer stack
+per step, batch 16, replayed as one captured graph).
 """
 from __future__ import annotations
 
@@ -166,21 +170,26 @@ class Workload:
         main.wait_stream(s_att)
 
 
-def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bool = False) -> float:
-    """Seconds for exactly `steps` steps (after `warmup` untimed ones)."""
+def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bool = False,
+               regions: int = 1) -> list:
+    """Seconds for exactly `steps` steps (after `warmup` untimed ones), measured `regions`
+    times over: one entry per timed region, each bracketed by a device synchronisation."""
     torch = wl.torch
     # steps per captured graph: one rotation over the copies, and at least 24 so that the
     # launch of the graph itself stays a small part of a replay
     # (layer-ahead: exactly one rotation, so that no copy - standing in for a layer - is used
     # twice inside a graph and has to wait for its own previous use)
     n = 1 if wl.layers_per_step != 1 else len(wl.slots) * (1 if layer_ahead else max(1, -(-24 // len(wl.slots))))
+    out = []
     if mode == "eager":
         wl.run(warmup, layer_ahead)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        wl.run(steps, layer_ahead)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        for _ in range(regions):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            wl.run(steps, layer_ahead)
+            torch.cuda.synchronize()
+            out.append(time.perf_counter() - t0)
+        return out
     # graph mode: one captured rotation (n steps), plus a tail graph if steps % n != 0
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -200,14 +209,21 @@ def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bo
     g_tail = capture(tail) if tail else None
     for _ in range(max(1, warmup // n)):
         (g_full or g_tail).replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(full):
-        g_full.replay()
-    if g_tail is not None:
-        g_tail.replay()
-    torch.cuda.synchronize()
-    return time.perf_counter() - t0
+    for _ in range(regions):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(full):
+            g_full.replay()
+        if g_tail is not None:
+            g_tail.replay()
+        torch.cuda.synchronize()
+        out.append(time.perf_counter() - t0)
+    return out
+
+
+def median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2])
 
 
 def time_kernels(wl: Workload, reps: int) -> dict:
@@ -344,34 +360,43 @@ def cpu_baseline(cfg, L, budget_s: float = 12.0, meta: str = None) -> dict:
 
 
 def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, meta=None,
-            layer_ahead=False) -> dict:
+            layer_ahead=False, cpu_budget_s: float = 12.0) -> dict:
     ab = algorithmic_bytes(cfg, 1 if meta == "fp8" else None)
     if copies is None:
         copies = max(2, int(-(-3 * CACHE_BYTES // ab["step"])))   # rotation >= 3x the caches
         copies = min(copies, 32)
     wl = Workload(cfg, copies, log, meta)
-    sec = time_steps(wl, steps, warmup, mode)
-    ms_step = sec / steps * 1e3
     layers = wl.layers_per_step
+    # The timed region is exactly `steps` steps; it is measured several times over (so that at
+    # least ~200 steps are timed in all, whatever `steps` is) and the median region counts.
+    regions = max(3, min(25, -(-200 // max(1, steps * layers))))
+    secs = time_steps(wl, steps, warmup, mode, regions=regions)
+    sec = median(secs)
+    ms_step = sec / steps * 1e3
     us_layer = ms_step * 1e3 / layers
+    region_us = sorted(x / steps * 1e6 / layers for x in secs)
     kern = time_kernels(wl, max(steps, 50))
     meta_build = time_build_metadata(wl)
-    spread = time_step_spread(wl, max(steps, 50))
+    spread = time_step_spread(wl, max(steps, 50) if layers == 1 else max(3, min(steps, 10)))
     # warm-cache figure for reference: the same step repeated on one copy
     one = Workload.__new__(Workload)
     one.__dict__.update(wl.__dict__)
     one.slots = wl.slots[:1] if layers == 1 else wl.slots
-    warm_ms = time_steps(one, steps, warmup, mode) / steps * 1e3 if layers == 1 else None
+    warm_ms = median(time_steps(one, steps, warmup, mode, regions=3)) / steps * 1e3 if layers == 1 else None
     # the same steps issued layer-ahead (prediction of later layers overlapping the
     # selection and attention of earlier ones); with a one-layer workload the rotating
     # copies stand in for the successive layers of a model
-    ahead_ms = time_steps(wl, steps, warmup, mode, layer_ahead=True) / steps * 1e3 if layer_ahead else None
+    ahead_ms = (median(time_steps(wl, steps, warmup, mode, layer_ahead=True, regions=3)) / steps * 1e3
+                if layer_ahead else None)
     dom = max(("predict", "attn"), key=lambda k: kern[k])
     achieved = ab[dom] / (kern[dom] * 1e-6) / 1e9
     res = {
         "tokens_per_s": cfg.batch / (ms_step * 1e-3),
         "ms_per_step": ms_step,
         "us_per_layer": us_layer,
+        "timed_regions": {"count": regions, "steps_each": steps,
+                          "us_per_layer_min": region_us[0], "us_per_layer_median": us_layer,
+                          "us_per_layer_max": region_us[-1]},
         "step_gbps": ab["step"] * layers / (ms_step * 1e-3) / 1e9,
         "kernel_us": kern,
         "dominant": dom,
@@ -389,11 +414,17 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
             "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
     if want_cpu:
-        res["cpu_baseline"] = cpu_baseline(cfg, wl.host0, meta=meta)
+        res["cpu_baseline"] = cpu_baseline(cfg, wl.host0, budget_s=cpu_budget_s, meta=meta)
     del wl, one
     import torch
     torch.cuda.empty_cache()
     return res
+
+
+def describe(cfg, meta=None) -> str:
+    return (f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv d={cfg.head_dim} N={cfg.ctx_len} b={cfg.batch} "
+            f"r={cfg.rank} G={cfg.group_size} M={cfg.n_select} layers={cfg.layers} {cfg.dtype}"
+            + (" joint-head" if cfg.joint else "") + (" fp8-metadata" if meta else ""))
 
 
 def main() -> int:
@@ -401,12 +432,13 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=24)
-    ap.add_argument("--config", default="c2",
+    ap.add_argument("--config", default="c4",
                     choices=["c1", "c2", "c3", "c4", "c5", "c1j", "c2j", "c3j", "c4j", "c5j"],
                     help="workload; a trailing j = the same workload under the joint-head design")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--copies", type=int, default=None, help="rotating input copies (default: 3x the caches)")
-    ap.add_argument("--extra", default="c3,c4", help="further configs reported under 'other_workloads' ('' = none)")
+    ap.add_argument("--extra", default="c1,c2,c3,c5",
+                    help="further configs reported under 'other_workloads' ('' = none)")
     ap.add_argument("--meta", default="same", choices=["same", "fp8"],
                     help="dtype of the compressed K cache: that of the workload, or 8-bit E4M3")
     ap.add_argument("--layer-ahead", dest="layer_ahead", action="store_true", default=True,
@@ -460,13 +492,24 @@ def main() -> int:
     others = {}
     for name in [x for x in args.extra.split(",") if x and x != args.config]:
         c = PRESETS[name]
-        st = max(20, min(args.steps, 60))
-        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log, want_cpu=False, meta=meta,
-                    layer_ahead=args.layer_ahead)
-        others[name] = {k: r[k] for k in ("tokens_per_s", "us_per_layer", "step_gbps", "kernel_us",
-                                          "roofline", "copies", "layer_ahead", "build_metadata",
-                                          "us_per_layer_spread")}
-        others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
+        # c5: a step is the whole 36-layer stack, replayed as one captured graph of 108 launches
+        st = max(10, min(args.steps, 20)) if c.layers > 1 else max(20, min(args.steps, 60))
+        r = measure(c, st, max(4, min(args.warmup, 8)), args.mode, None, log,
+                    want_cpu=not args.no_cpu_baseline, meta=meta, layer_ahead=args.layer_ahead,
+                    cpu_budget_s=3.0)
+        keep = ["tokens_per_s", "ms_per_step", "us_per_layer", "timed_regions", "kernel_us", "copies",
+                "layer_ahead", "us_per_layer_spread", "algorithmic_bytes"]
+        if name.startswith("c1"):
+            # 0.8 MB per step: bound by launch and memory latency, latency reported only
+            others[name] = {k: r[k] for k in keep}
+            others[name]["roofline"] = None
+            others[name]["note"] = "latency-bound (0.8 MB per step): microseconds only, no roofline claim"
+        else:
+            others[name] = {k: r[k] for k in keep + ["step_gbps", "roofline", "build_metadata"]}
+            others[name]["step_hbm_frac"] = r["step_gbps"] / HBM_PEAK_GBPS
+        if "cpu_baseline" in r:
+            others[name]["cpu_baseline"] = r["cpu_baseline"]
+        others[name]["workload"] = describe(c, meta)
 
     line = {
         "metric": METRIC,
@@ -482,15 +525,11 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": cfg.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv d={cfg.head_dim} "
-                               f"N={cfg.ctx_len} b={cfg.batch} r={cfg.rank} G={cfg.group_size} "
-                               f"M={cfg.n_select} layers={cfg.layers} {cfg.dtype}"
-                               + (" joint-head" if cfg.joint else "")
-                               + (" fp8-metadata" if meta else ""),
-                   "mode": args.mode, "input_copies": main_res["copies"]},
+        "config": {"workload": describe(cfg, meta), "mode": args.mode, "input_copies": main_res["copies"]},
         "step_hbm_gbps": main_res["step_gbps"],
         "step_hbm_frac": main_res["step_gbps"] / HBM_PEAK_GBPS,
         "warm_ms_per_step": main_res["warm_ms_per_step"],
+        "timed_regions": main_res["timed_regions"],
         "us_per_layer_spread": main_res["us_per_layer_spread"],
         "layer_ahead": main_res["layer_ahead"],
         "build_metadata": main_res["build_metadata"],
