@@ -251,6 +251,51 @@ def full_size_sampled(cfg: Config, samples, budgets=None, layer=0, meta: str = N
 
 
 
+def full_size_all(cfg: Config, layer=0, threads: int = 16):
+    """GPU on the whole batch at the real size, oracle on EVERY (b, k) problem (its own
+    threading over the independent problems).  The oracle's metadata is what both sides
+    score.  Returns (problems, problems compared by exact set equality, worst attention
+    error)."""
+    import time
+    t0 = time.time()
+    L = make_layer(cfg, layer, workers=16)
+    D = DeviceLayer(L)
+    p = kv_params(cfg)
+    sh = orc_shape(cfg, n_threads=threads)
+    B, Hk, N, r = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank
+    klr_gpu = torch.empty((B, Hk, N, r), dtype=kv.binding._dtype_of(p.meta_dtype), device=DEV)
+    kv.kvs_build_metadata(p, D.K, D.A, klr_gpu)
+    torch.cuda.synchronize()
+    klr_ref, klr_exact = oracle.build_metadata(sh, L.K, L.A, want_exact=True)
+    klr_gpu_h = to_host_storage(klr_gpu)
+    worst_frac = 0.0
+    for b in range(B):
+        for k in range(Hk):
+            absdot = np.abs(storage_to_f32(L.K[b, k])).astype(np.float64) @ np.abs(L.A[k]).astype(np.float64)
+            worst_frac = max(worst_frac, compare_metadata(klr_gpu_h[b, k], klr_ref[b, k], klr_exact[b, k],
+                                                          absdot, cfg.head_dim, cfg.dtype))
+    del klr_exact, klr_gpu_h
+    ws = workspace(p)
+    idx = torch.full((B, Hk, cfg.n_select), -1, dtype=torch.int32, device=DEV)
+    out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=D.q.dtype, device=DEV)
+    kv.kvs_decode_step(p, D.q, to_dev(klr_ref), D.A, D.K, D.V, idx, None, out, ws)
+    torch.cuda.synchronize()
+    idx_h, out_h = idx.cpu().numpy(), out_values(out)
+    ref = oracle.predict_select(sh, L.q, klr_ref, L.A)
+    exact = 0
+    for b in range(B):
+        for k in range(Hk):
+            if check_index_margin(idx_h[b, k], ref["gs"][b, k], ref["boundary"][b, k], f"{cfg.name} b={b} k={k}"):
+                np.testing.assert_array_equal(idx_h[b, k], ref["idx"][b, k])
+                exact += 1
+    out_ref = oracle.sparse_attn(sh, L.q, L.K, L.V, idx_h)
+    err = attn_error(out_h, out_ref)
+    assert err <= ATTN_TOL[cfg.dtype], (cfg.name, err)
+    print(f"[parity] {cfg.name}_full_all: {B * Hk} problems, {exact} by exact set equality, "
+          f"attention err {err:.3g}, metadata mismatch <= {worst_frac:.2g}, {time.time() - t0:.1f} s", flush=True)
+    return B * Hk, exact, err
+
+
 def _ulp(v: np.ndarray, dtype: str) -> np.ndarray:
     """Spacing of the storage dtype at |v| (normal range; E4M3 also below it)."""
     if dtype == "f32":
