@@ -105,7 +105,9 @@ typedef enum {
   KVS_ERR_UNSUPPORTED = 4, /* consistent but outside the supported set        */
   KVS_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small         */
   KVS_ERR_DEVICE = 6,      /* a HIP launch reported an error                  */
-  KVS_ERR_ALIGN = 7        /* a tensor pointer is not 16-byte aligned         */
+  KVS_ERR_ALIGN = 7,       /* a tensor pointer is not 16-byte aligned         */
+  KVS_ERR_SCRATCH = 8      /* kvs_decode_step_static: the problem needs more scratch than
+                              KVS_STATIC_SCRATCH_BYTES                        */
 } kvs_status;
 
 typedef enum { KVS_F32 = 0, KVS_BF16 = 1, KVS_FP8_E4M3 = 2 /* meta_dtype only */ } kvs_dtype;
@@ -252,6 +254,27 @@ kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_
                               const void* rb_V, int32_t rb_len, int32_t rb_capacity,
                               int32_t* idx, float* group_scores, void* out, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): kvs_decode_step without a workspace argument.
+ * The scratch memory of the step's kernels lives in a static device array inside the
+ * library, KVS_STATIC_SCRATCH_BYTES per GPU, held by every GPU the library runs on until
+ * the process ends.  The call allocates and frees nothing (no hipMalloc, no hipFree, no
+ * allocating library routine) and does not synchronise; it enqueues one small fill kernel
+ * that zeroes the counter area, then the launches of kvs_decode_step, on `stream`.  Params
+ * whose kvs_workspace_bytes() exceeds KVS_STATIC_SCRATCH_BYTES are refused with
+ * KVS_ERR_SCRATCH before anything is launched (every workload of the evaluation fits: the
+ * largest, 128 problems of 4096 groups, needs 4.6 MiB).  The device that `stream` belongs to
+ * must be the current device.  On the first call per device the library looks up that
+ * device's address of the array; make that first call outside a graph capture.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, or graphs replayed concurrently) race and give undefined results;
+ * calls ordered on one stream are safe, whatever their shapes.  Results are bit-identical
+ * to kvs_decode_step's. */
+#define KVS_STATIC_SCRATCH_BYTES (8u << 20)
+kvs_status kvs_decode_step_static(const kvs_params* p, const void* q, const void* K_lr,
+                                  const float* A, const void* K, const void* V, int32_t* idx,
+                                  float* group_scores, void* out, void* stream);
 
 /* Static, NUL-terminated description of a status code (host pointer). */
 const char* kvs_status_str(kvs_status s);

@@ -16,13 +16,14 @@ from . import build as _build
 KVS_F32, KVS_BF16, KVS_FP8_E4M3 = 0, 1, 2
 KVS_REDUCE_MAX, KVS_REDUCE_MEAN = 0, 1
 KVS_HEADS_SEPARATE, KVS_HEADS_JOINT = 0, 1
+KVS_STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = (
     "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata",
     "kvs_build_metadata_rows", "kvs_append_group", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
     "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_sparse_decode_attn_paged",
-    "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb",
+    "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb", "kvs_decode_step_static",
     "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
@@ -138,6 +139,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_sparse_decode_attn.restype = ctypes.c_int
     lib.kvs_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_decode_step.restype = ctypes.c_int
+    lib.kvs_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.kvs_decode_step_static.restype = ctypes.c_int
     lib.kvs_status_str.argtypes = [ctypes.c_int]
     lib.kvs_status_str.restype = ctypes.c_char_p
     lib.kvs_last_device_error.argtypes = []
@@ -396,6 +399,15 @@ def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspa
     c = p._c()
     head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream)
     _check(load_library().kvs_decode_step(ctypes.byref(c), *head, *tail), "kvs_decode_step")
+
+
+def kvs_decode_step_static(p: Params, q, K_lr, A, K, V, idx, group_scores, out, stream=None) -> None:
+    """kvs_decode_step on the library's own static scratch memory (no workspace argument)."""
+    c = p._c()
+    head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, None, stream)
+    # tail = [idx, group_scores, out, workspace, workspace_bytes, stream]
+    _check(load_library().kvs_decode_step_static(ctypes.byref(c), *head, *tail[:3], tail[5]),
+           "kvs_decode_step_static")
 
 
 def kvs_decode_step_rb(p: Params, q, K_lr, A, K, V, rb_K, rb_V, rb_len, idx, group_scores, out,

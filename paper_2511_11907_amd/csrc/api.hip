@@ -2,6 +2,8 @@
 // declared in include/kvswap_hip.h.  Everything here runs on the host; all checks
 // are done before the first launch.
 #include <math.h>
+
+#include <mutex>
 #ifdef KVS_TUNING
 #include <stdlib.h>
 #endif
@@ -361,6 +363,63 @@ kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
                             workspace, workspace_bytes, stream);
 }
 
+}  // extern "C"
+
+// ---- a whole decode step for callers that cannot allocate ------------------------------------
+// The scratch memory of the step's kernels (arrival counters, score histograms, group scores,
+// split partial results) lives in a device array of the library itself instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy of the array, at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, never a
+// device address.
+static __device__ __align__(256) unsigned char scratch[KVS_STATIC_SCRATCH_BYTES];
+
+namespace kvs {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, looked up once
+
+// Address of the current device's copy of the array (set-up on the first call per device).
+kvs_status static_scratch(void** ptr_out) {
+  int device = -1;
+  kvs_status s = dev(hipGetDevice(&device));
+  if (s != KVS_OK) return s;
+  if (device < 0 || device >= kMaxDevices) return KVS_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    if ((s = dev(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)))) != KVS_OK) return s;
+    if (!ptr) return KVS_ERR_DEVICE;
+    g_scratch_ptr[device] = ptr;
+  }
+  *ptr_out = g_scratch_ptr[device];
+  return KVS_OK;
+}
+
+}  // namespace
+}  // namespace kvs
+
+extern "C" {
+
+kvs_status kvs_decode_step_static(const kvs_params* p, const void* q, const void* K_lr,
+                                  const float* A, const void* K, const void* V, int32_t* idx,
+                                  float* group_scores, void* out, void* stream) {
+  if (!p || !q || !K_lr || !A || !K || !V || !idx || !out) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  const Plan pl = make_plan(*p);
+  if (pl.total_bytes > (size_t)KVS_STATIC_SCRATCH_BYTES) return KVS_ERR_SCRATCH;
+  void* ptr = nullptr;
+  if ((s = static_scratch(&ptr)) != KVS_OK) return s;
+  // The array keeps whatever the last call on this device left (possibly of another shape,
+  // whose counter area was laid out differently): the counters of this call start at zero.
+  if ((s = dev(launch_fill_zero((char*)ptr + pl.off_sync, pl.sync_bytes, (hipStream_t)stream))) != KVS_OK)
+    return s;
+  return kvs_decode_step(p, q, K_lr, A, K, V, idx, group_scores, out, ptr,
+                         (size_t)KVS_STATIC_SCRATCH_BYTES, stream);
+}
+
 const char* kvs_status_str(kvs_status s) {
   switch (s) {
     case KVS_OK: return "ok";
@@ -371,6 +430,7 @@ const char* kvs_status_str(kvs_status s) {
     case KVS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case KVS_ERR_DEVICE: return "HIP launch failed";
     case KVS_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+    case KVS_ERR_SCRATCH: return "the problem needs more scratch memory than the library's static buffer holds";
   }
   return "unknown status";
 }

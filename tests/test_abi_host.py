@@ -12,7 +12,7 @@ from paper_2511_11907_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "kvswap_hip.h")
 
-OK, E_NULL, E_SHAPE, E_DTYPE, E_UNSUP, E_WS, E_DEV, E_ALIGN = range(8)
+OK, E_NULL, E_SHAPE, E_DTYPE, E_UNSUP, E_WS, E_DEV, E_ALIGN, E_SCRATCH = range(9)
 
 
 def _declared():
@@ -35,8 +35,8 @@ def test_python_binding_has_the_same_names_as_the_header():
 
 
 def test_status_strings():
-    seen = {kv.kvs_status_str(i) for i in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {kv.kvs_status_str(i) for i in range(9)}
+    assert len(seen) == 9 and "ok" in seen
     assert kv.kvs_status_str(99) == "unknown status"
 
 
@@ -220,3 +220,23 @@ def test_reciprocal_division_used_by_the_attention_kernels_is_exact():
         assert recip < (1 << 32)
         for x in (pos, edge):
             assert np.array_equal((x * recip) >> np.uint64(32), x // np.uint64(G)), G
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit_before_any_launch():
+    """kvs_decode_step_static: NULL pointers, bad params and problems whose scratch memory
+    exceeds the library's static buffer are refused on the host (fake addresses, no GPU)."""
+    lib = kv.load_library()
+    fake, null = ctypes.c_void_p(0x10000), ctypes.c_void_p(0)
+    call = lambda p, *a: lib.kvs_decode_step_static(ctypes.byref(p._c()), *a)
+    ok = _p()
+    assert kv.kvs_workspace_bytes(ok) <= kv.KVS_STATIC_SCRATCH_BYTES
+    assert call(ok, null, fake, fake, fake, fake, fake, null, fake, null) == E_NULL
+    assert call(ok, fake, fake, fake, fake, fake, fake, null, null, null) == E_NULL
+    assert call(_p(n_select=0), fake, fake, fake, fake, fake, fake, null, fake, null) == E_SHAPE
+    big = _p(batch=64)     # 512 problems: histograms and scores alone exceed the buffer
+    assert kv.kvs_workspace_bytes(big) > kv.KVS_STATIC_SCRATCH_BYTES
+    assert call(big, fake, fake, fake, fake, fake, fake, null, fake, null) == E_SCRATCH
+    # the header's constant and the binding's agree
+    text = open(HEADER).read()
+    assert re.search(r"#define\s+KVS_STATIC_SCRATCH_BYTES\s+\(8u\s*<<\s*20\)", text)
+    assert kv.KVS_STATIC_SCRATCH_BYTES == 8 << 20
