@@ -138,6 +138,18 @@ size_t kvs_workspace_bytes(const kvs_params* p);
 kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* Diagnostic: has a wait between workgroups of kvs_decode_step_single_launch ever run out on this
+ * workspace since it was prepared?  Copies one word to the host and SYNCHRONISES `stream`.
+ * KVS_OK if not; KVS_ERR_DEVICE if so (text in kvs_last_device_error): results of that step
+ * are incomplete and the workspace needs kvs_workspace_init before it is used again. */
+kvs_status kvs_workspace_check(const kvs_params* p, const void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/* Bound of the waits between workgroups inside kvs_decode_step_single_launch, in polls of a counter (a
+ * poll takes one to two microseconds); process-wide, takes effect with the next call;
+ * polls <= 0 restores the default (about a second).  Meant for tests and diagnostics. */
+void kvs_set_wait_limit(int32_t polls);
+
 /* Validate params without touching a device: KVS_OK or the error the other
  * calls would return for them. */
 kvs_status kvs_check_params(const kvs_params* p);
@@ -246,6 +258,29 @@ kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr,
                            const float* A, const void* K, const void* V, int32_t* idx,
                            float* group_scores, void* out, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/* The same step as ONE launch: a persistent grid whose workgroups draw prediction, selection
+ * and attention work items of all (sequence, KV head) problems from one counter, ordered so
+ * that the selection of a problem runs while other problems stream and no phase waits for a
+ * launch boundary.  Items wait for the items they depend on through counters in the
+ * workspace; such a wait is bounded (kvs_set_wait_limit) and cannot block the grid (an item
+ * only waits for items drawn before it, which running workgroups hold).  Should a wait run
+ * out all the same, the step's results are incomplete, the error word of the workspace is
+ * set (kvs_workspace_check) and the workspace must be prepared again.
+ * Covers the layouts of the evaluated models' layers only - bf16 K/V and metadata, d = 128,
+ * four query heads per KV head, r = 32 with G = 4 or r = 64 with G = 8, per-head adapters,
+ * at most 16384 groups and 4096 selected groups per problem - and returns
+ * KVS_ERR_UNSUPPORTED for every other.  Scores and selection are bit for bit those of
+ * kvs_decode_step; `out` may differ from it in the last bits (the selected tokens are cut
+ * into another number of splits, i.e. summed in another order) and is the same from call to
+ * call.  On MI355X it is SLOWER than the three launches at every evaluated size (inside a
+ * grid that saturates the memory system every dependent step of the selection takes several
+ * times longer, and the attention of a problem still has to wait for it): kvs_decode_step
+ * does not use it.  It is kept for callers to whom the number of launches matters more. */
+kvs_status kvs_decode_step_single_launch(const kvs_params* p, const void* q, const void* K_lr,
+                                         const float* A, const void* K, const void* V, int32_t* idx,
+                                         float* group_scores, void* out, void* workspace,
+                                         size_t workspace_bytes, void* stream);
 
 /* kvs_decode_step with the rolling buffer in the attention (kvs_predict_select, then
  * kvs_sparse_decode_attn_rb). */

@@ -19,11 +19,13 @@ KVS_HEADS_SEPARATE, KVS_HEADS_JOINT = 0, 1
 KVS_STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = (
-    "kvs_workspace_bytes", "kvs_workspace_init", "kvs_check_params", "kvs_build_metadata",
+    "kvs_workspace_bytes", "kvs_workspace_init", "kvs_workspace_check", "kvs_set_wait_limit",
+    "kvs_check_params", "kvs_build_metadata",
     "kvs_build_metadata_rows", "kvs_append_group", "kvs_predict_select",
     "kvs_predict_scores", "kvs_select_topk",
     "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_sparse_decode_attn_paged",
     "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb", "kvs_decode_step_static",
+    "kvs_decode_step_single_launch",
     "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
@@ -112,6 +114,10 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_workspace_bytes.restype = sz
     lib.kvs_workspace_init.argtypes = [pp, vp, sz, vp]
     lib.kvs_workspace_init.restype = ctypes.c_int
+    lib.kvs_workspace_check.argtypes = [pp, vp, sz, vp]
+    lib.kvs_workspace_check.restype = ctypes.c_int
+    lib.kvs_set_wait_limit.argtypes = [ctypes.c_int32]
+    lib.kvs_set_wait_limit.restype = None
     lib.kvs_check_params.argtypes = [pp]
     lib.kvs_check_params.restype = ctypes.c_int
     lib.kvs_build_metadata.argtypes = [pp, vp, vp, vp, vp]
@@ -139,6 +145,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_sparse_decode_attn.restype = ctypes.c_int
     lib.kvs_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_decode_step.restype = ctypes.c_int
+    lib.kvs_decode_step_single_launch.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_decode_step_single_launch.restype = ctypes.c_int
     lib.kvs_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kvs_decode_step_static.restype = ctypes.c_int
     lib.kvs_status_str.argtypes = [ctypes.c_int]
@@ -223,6 +231,17 @@ def kvs_workspace_init(p: Params, workspace, stream=None) -> None:
     ws, nws = _ws(workspace)
     _check(load_library().kvs_workspace_init(ctypes.byref(c), ws, nws, _stream(stream)),
            "kvs_workspace_init")
+
+
+def kvs_workspace_check(p: Params, workspace, stream=None) -> int:
+    """Status code (0, or 6 if a wait inside kvs_decode_step ever ran out); synchronises the stream."""
+    c = p._c()
+    ws, nws = _ws(workspace)
+    return int(load_library().kvs_workspace_check(ctypes.byref(c), ws, nws, _stream(stream)))
+
+
+def kvs_set_wait_limit(polls: int) -> None:
+    load_library().kvs_set_wait_limit(int(polls))
 
 
 def _metadata_args(p: Params, K, A, K_lr):
@@ -399,6 +418,12 @@ def kvs_decode_step(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspa
     c = p._c()
     head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream)
     _check(load_library().kvs_decode_step(ctypes.byref(c), *head, *tail), "kvs_decode_step")
+
+
+def kvs_decode_step_single_launch(p: Params, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream=None) -> None:
+    c = p._c()
+    head, tail = _step_args(p, q, K_lr, A, K, V, idx, group_scores, out, workspace, stream)
+    _check(load_library().kvs_decode_step_single_launch(ctypes.byref(c), *head, *tail), "kvs_decode_step_single_launch")
 
 
 def kvs_decode_step_static(p: Params, q, K_lr, A, K, V, idx, group_scores, out, stream=None) -> None:

@@ -58,6 +58,12 @@ Plan make_plan(const kvs_params& p) {
     const int chunks = want < 1 ? 1 : (want > most ? most : want);
     pl.predict_units_per_wg = round_up(ceil_div(pl.predict_units, chunks), kPredictUnitsPerWgStep);
     pl.predict_chunks = ceil_div(pl.predict_units, pl.predict_units_per_wg);
+    // single-launch step: two prediction items per workgroup slot
+    const int want_s = ceil_div(target("KVS_STEP_PREDICT_ITEMS", 2 * kStepTargetWgs), pl.sets);
+    const int most_s = ceil_div(pl.predict_units, kStepPredictUnitsPerWgStep);
+    const int chunks_s = want_s < 1 ? 1 : (want_s > most_s ? most_s : want_s);
+    pl.step_predict_units_per_wg = round_up(ceil_div(pl.predict_units, chunks_s), kStepPredictUnitsPerWgStep);
+    pl.step_predict_chunks = ceil_div(pl.predict_units, pl.step_predict_units_per_wg);
   }
 
   // attention: split the selected tokens of a problem over workgroups
@@ -75,21 +81,31 @@ Plan make_plan(const kvs_params& p) {
     // 7 splits of 128 units out of 820 where 8 of 104 fill the chip evenly)
     pl.attn_units_per_split = round_up(ceil_div(pl.attn_units, splits), kAttnUnitsPerWave);
     pl.attn_splits = ceil_div(pl.attn_units, pl.attn_units_per_split);
+    int step = ceil_div(target("KVS_STEP_ATTN_WGS", kStepTargetWgs), pl.problems);
+    step = step < 1 ? 1 : (step > most ? most : step);
+    if (step > kAttnMaxSplitsPerProblem) step = kAttnMaxSplitsPerProblem;
+    pl.step_attn_units_per_split = round_up(ceil_div(pl.attn_units, step), kAttnUnitsPerWave);
+    pl.step_attn_splits = ceil_div(pl.attn_units, pl.step_attn_units_per_split);
   }
 
   size_t off = 0;
-  // zero-on-entry area: [0, P) attention arrival counters, then one histogram of
-  // kSelectHistBins counters per selection set
+  // zero-on-entry area: three counters per problem and the launch-wide words of the
+  // single-launch step, then one histogram of kSelectHistBins counters per selection set
   pl.off_sync = off;
-  pl.off_hist = align256((size_t)pl.problems * sizeof(int));
+  pl.sync_arrivals = 0;
+  pl.sync_pred_done = pl.problems;
+  pl.sync_sel_done = 2 * pl.problems;
+  pl.sync_ticket = 3 * pl.problems;
+  pl.off_hist = align256((size_t)(3 * pl.problems + 4) * sizeof(int));
   pl.sync_bytes = pl.off_hist + align256((size_t)pl.sets * kSelectHistBins * sizeof(int));
   off += pl.sync_bytes;
   pl.off_gs = off;
-  off += align256((size_t)pl.sets * pl.n_groups * sizeof(float));
+  off += align256(((size_t)pl.sets * pl.n_groups + kSelectScorePad) * sizeof(float));
   pl.off_part_ml = off;
-  off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * 2 * sizeof(float));
+  const int most_splits = pl.attn_splits > pl.step_attn_splits ? pl.attn_splits : pl.step_attn_splits;
+  off += align256((size_t)pl.problems * most_splits * pl.q_per_kv * 2 * sizeof(float));
   pl.off_part_o = off;
-  off += align256((size_t)pl.problems * pl.attn_splits * pl.q_per_kv * p.head_dim * sizeof(float));
+  off += align256((size_t)pl.problems * most_splits * pl.q_per_kv * p.head_dim * sizeof(float));
   pl.off_qlr = off;  // low-rank queries of the joint-head mode
   off += align256((size_t)pl.sets * p.rank * sizeof(float));
   pl.total_bytes = off;
@@ -183,6 +199,27 @@ kvs_status kvs_workspace_init(const kvs_params* p, void* workspace, size_t works
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   return dev(launch_fill_zero((char*)workspace + pl.off_sync, pl.sync_bytes, (hipStream_t)stream));
 }
+
+kvs_status kvs_workspace_check(const kvs_params* p, const void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  if (!p) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  const Plan pl = make_plan(*p);
+  if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+  const int* word = (const int*)((const char*)workspace + pl.off_sync) + pl.sync_ticket + 2;
+  int flag = 0;
+  if ((s = dev(hipMemcpyAsync(&flag, word, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream))) != KVS_OK)
+    return s;
+  if ((s = dev(hipStreamSynchronize((hipStream_t)stream))) != KVS_OK) return s;
+  if (flag != 0) {
+    g_last_device_error = "a wait between workgroups of kvs_decode_step_single_launch ran out; results of that call are incomplete";
+    return KVS_ERR_DEVICE;
+  }
+  return KVS_OK;
+}
+
+void kvs_set_wait_limit(int32_t polls) { set_fused_wait_limit(polls); }
 
 kvs_status kvs_build_metadata_rows(const kvs_params* p, const void* K, const float* A, void* K_lr,
                                    int32_t first_row, int32_t n_rows, void* stream) {
@@ -296,7 +333,7 @@ kvs_status attend(const kvs_params* p, const void* q, const void* K, const void*
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
   float* part_o = (float*)((char*)workspace + pl.off_part_o);
-  int* arrivals = (int*)((char*)workspace + pl.off_sync);
+  int* arrivals = (int*)((char*)workspace + pl.off_sync) + pl.sync_arrivals;
   return dev(launch_attn(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, slot_table,
                          (hipStream_t)stream));
 }
@@ -354,6 +391,25 @@ kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_
   if (s != KVS_OK) return s;
   return kvs_sparse_decode_attn_rb(p, q, K, V, idx, rb_K, rb_V, rb_len, rb_capacity, out,
                                    workspace, workspace_bytes, stream);
+}
+
+kvs_status kvs_decode_step_single_launch(const kvs_params* p, const void* q, const void* K_lr,
+                                         const float* A, const void* K, const void* V, int32_t* idx,
+                                         float* group_scores, void* out, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  if (!p || !q || !K_lr || !A || !K || !V || !idx || !out) return KVS_ERR_NULL;
+  kvs_status s = check_params(p, true);
+  if (s != KVS_OK) return s;
+  if (misaligned(q) || misaligned(K_lr) || misaligned(A) || misaligned(K) || misaligned(V) ||
+      misaligned(idx) || misaligned(out) || (group_scores && misaligned(group_scores)))
+    return KVS_ERR_ALIGN;
+  const Plan pl = make_plan(*p);
+  if (!fused_step_applies(*p, pl)) return KVS_ERR_UNSUPPORTED;
+  if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
+  char* ws = (char*)workspace;
+  return dev(launch_fused_step(*p, pl, q, K_lr, A, K, V, (float*)(ws + pl.off_gs), group_scores, idx,
+                               (float*)(ws + pl.off_part_ml), (float*)(ws + pl.off_part_o), out,
+                               (int*)(ws + pl.off_sync), (hipStream_t)stream));
 }
 
 kvs_status kvs_decode_step(const kvs_params* p, const void* q, const void* K_lr, const float* A,

@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
 
   // per-wave partial states, merged by the whole workgroup at the end
   __shared__ AttnWaveStates<D, QPK> ws;
+  __shared__ AttnMergeShared<QPK> ms;
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int split = blockIdx.x, p = blockIdx.y;
@@ -277,7 +278,7 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
       for (int e = 0; e < EPL; ++e) ws.o[wave][AttnWaveStates<D, QPK>::pos(h, c * EPL + e)] = o[h][e];
     }
   }
-  attn_merge_and_finish<E, D, QPK>(ws, part_ml, part_o,
+  attn_merge_and_finish<E, D, QPK>(ws, ms, part_ml, part_o,
                                    out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D, arrivals, p,
                                    split, n_splits);
   KVS_ATTN_TRACE(6);

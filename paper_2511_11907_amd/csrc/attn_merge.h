@@ -74,14 +74,23 @@ struct AttnWaveStates {
   float o[kAttnWaves][kWords];
 };
 
+// LDS of the merge over the splits (used by the last workgroup of a problem only).
+template <int QPK>
+struct AttnMergeShared {
+  int last;
+  float cw[kAttnMaxSplits][QPK];  // weight of each split, per head
+  float cl[QPK];                  // merged softmax denominators
+};
+
 // Every lane of the workgroup calls this after its wave's state is written to `ws` (no
 // barrier needed before the call).  p: problem (sequence, KV head); op: the QPK output
-// rows of this problem.
+// rows of this problem.  Returns true (on all lanes) in the workgroup that wrote the
+// problem's output: the only one, or the one that arrived last.
 template <typename E, int D, int QPK>
-__device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws, float* part_ml,
-                                                      float* part_o, typename E::storage* op,
-                                                      int* __restrict__ arrivals, int p, int split,
-                                                      int n_splits) {
+__device__ __forceinline__ bool attn_merge_and_finish(AttnWaveStates<D, QPK>& ws, AttnMergeShared<QPK>& ms,
+                                                      float* part_ml, float* part_o,
+                                                      typename E::storage* op, int* __restrict__ arrivals,
+                                                      int p, int split, int n_splits) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   auto& s_m = ws.m;
   auto& s_l = ws.l;
@@ -120,23 +129,23 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
       }
     }
   }
-  if (n_splits == 1) return;  // uniform
+  if (n_splits == 1) return true;  // uniform
 
   // ---- the last workgroup of the problem merges the splits ------------------------
-  __shared__ int s_last;
-  __shared__ float s_cw[kAttnMaxSplits][QPK];  // weight of each split, per head
-  __shared__ float s_cl[QPK];                  // merged softmax denominators
+  int& s_last = ms.last;
+  auto& s_cw = ms.cw;
+  auto& s_cl = ms.cl;
   KVS_ATTN_TRACE(3);
   publish_complete_and_barrier();  // the partials are out before the arrival is announced
   KVS_ATTN_TRACE(4);
   if (tid == 0) {
     const int old = atomicAdd(&arrivals[p], 1);
     s_last = (old == n_splits - 1);
-    if (s_last) arrivals[p] = 0;  // leave the counter ready for the next call
+    if (s_last) publish_store(&arrivals[p], 0);  // leave the counter ready for the next call
   }
   lds_barrier();
   KVS_ATTN_TRACE(5);
-  if (!s_last) return;
+  if (!s_last) return false;
   consume_fence();
   const float* pml = part_ml + (size_t)p * n_splits * QPK * 2;
   for (int h = wave; h < QPK; h += kAttnWaves) {  // one wave per head, lanes over splits
@@ -199,6 +208,7 @@ __device__ __forceinline__ void attn_merge_and_finish(AttnWaveStates<D, QPK>& ws
     if constexpr (E::kBytes == 2) op[h * D + dd] = float_to_bf16_bits(r);
     else op[h * D + dd] = r;
   }
+  return true;
 }
 
 }  // namespace kvs

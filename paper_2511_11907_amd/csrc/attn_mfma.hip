@@ -28,244 +28,20 @@
 //   O^T      lane (c, g), register i of instruction b: head c, d = 8 (4g + i) + b.
 // Every lane therefore owns one head (c) from the logits to the output, so the running
 // maximum, the denominator and the rescaling of the accumulators stay in the lane.
-#include "attn_merge.h"
+#include "attn_mfma_item.h"
 
 KVS_ATTN_TRACE_ACCESSOR(kvs_debug_attn_mfma_trace)
 
 namespace kvs {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-
-constexpr int kMfmaD = 128;
-constexpr int kTileTokens = 16;                       // tokens per wave batch (= kAttnUnitsPerWave units)
-constexpr int kTokensPerUnit = kWave / (kMfmaD / 8);  // 4: the unit the split plan counts in
-static_assert(kAttnUnitsPerWave * kTokensPerUnit == kTileTokens, "a wave batch must be one tile");
-
-// two floats -> two bf16 in one register (round to nearest even; inputs are finite, >= 0)
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
-}
 
 // (registers: the plain and rolling-buffer modes fit the 128 that let two workgroups share a
 // compute unit; the mapping table's extra look-ahead does not, and a spilled register is
 // reloaded in order behind the key loads, i.e. stalls the value loads for a full latency,
 // so that mode takes what it needs)
 template <int QPK, int MODE, bool INTERLEAVE>
-__global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn_mfma_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ idx, float* part_ml, float* part_o, uint16_t* __restrict__ out,
-    int* __restrict__ arrivals, int n_kv_heads, int kv_heads_per_set, int ctx_rows, int M, int G,
-    int log2G, uint32_t recipG, int units, int units_per_split, int n_splits, float scale_log2e,
-    const uint16_t* __restrict__ rb_K, const uint16_t* __restrict__ rb_V, int rb_len, int rb_capacity,
-    const int32_t* __restrict__ slot_table, int n_groups) {
-  constexpr bool RB = MODE >= kAttnRolling;
-  constexpr bool PAGED = MODE == kAttnPaged;
-  constexpr int D = kMfmaD;
-  static_assert(QPK >= 1 && QPK <= 16, "the heads of a KV head are one 16-wide matrix dimension");
-
-  __shared__ AttnWaveStates<D, QPK> ws;
-
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // (tells the compiler it is uniform)
-  const int split = blockIdx.x, p = blockIdx.y;
-  KVS_ATTN_TRACE(0);
-#ifdef KVS_ATTN_TRACE_BUILD
-  if (threadIdx.x == 0)  // where the workgroup runs: XCC id (hwreg 20), HW id (hwreg 4)
-    g_attn_trace[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + 7) & 0xFFFF] =
-        ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
-#endif
-  const int b = p / n_kv_heads, k = p % n_kv_heads;
-  const int n_q_heads = n_kv_heads * QPK;
-  const int c = lane & 15;  // head (logits, output), token of the tile (keys), d block (values)
-  const int g = lane >> 4;  // contraction slice
-  const int n_tok = M * G;
-  const int n_all = RB ? n_tok + rb_len : n_tok;
-  auto group_of = [&](int tok) {
-    return log2G >= 0 ? tok >> log2G : (int)__umulhi((uint32_t)tok, recipG);
-  };
-
-  // Q^T operand: head c, d = 32 j + 8 g .. + 7
-  uint4 qb[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    qb[j] = make_uint4(0u, 0u, 0u, 0u);
-    if (c < QPK)
-      qb[j] = *reinterpret_cast<const uint4*>(q + ((size_t)b * n_q_heads + (size_t)k * QPK + c) * D + 32 * j + 8 * g);
-  }
-
-  const uint16_t* Kp = PAGED ? K : K + (size_t)p * ctx_rows * D;
-  const uint16_t* Vp = PAGED ? V : V + (size_t)p * ctx_rows * D;
-  const int32_t* tab = slot_table + (size_t)p * n_groups;  // (only read when PAGED)
-  const uint16_t* Kr = rb_K + (size_t)p * rb_capacity * D;
-  const uint16_t* Vr = rb_V + (size_t)p * rb_capacity * D;
-  const int32_t* sel = idx + (size_t)(p / kv_heads_per_set) * M;
-  // The units of a problem go to its splits either as one contiguous range each, or - for
-  // long problems - one workgroup step (a tile per wave) at a time, round-robin: every
-  // workgroup then walks the whole address range of the problem, and workgroups finish
-  // closer together (identical work takes a different time in different parts of a long
-  // cache: 4 % on the kernel at 128K tokens, nothing at 32K).  Either way the assignment
-  // is a fixed function of the launch, so results are reproducible bit for bit.
-  constexpr int kWgStep = kAttnWaves * kAttnUnitsPerWave;
-  const int u0 = INTERLEAVE ? split * kWgStep : split * units_per_split;
-  const int u1 = (INTERLEAVE || split == n_splits - 1) ? units : min(units, u0 + units_per_split);
-  const int kStep = INTERLEAVE ? n_splits * kWgStep : kWgStep;  // from one step of this workgroup to its next
-
-  // token t of the tile that starts at unit ub is attended iff its unit belongs to this
-  // split and it lies inside the list
-  auto attended = [&](int ub, int t) {
-    return (ub + t / kTokensPerUnit < u1) && (ub * kTokensPerUnit + t < n_all);
-  };
-  // Position t of the tile at unit ub in the attended-token list (positions that are not
-  // attended stand for position 0, one that is), and whether it lies in the rolling buffer.
-  auto position = [&](int ub, int t) { return attended(ub, t) ? ub * kTokensPerUnit + t : 0; };
-  auto in_buffer = [&](int tok) { return RB && tok >= n_tok; };
-  // Cache row of a position, in two steps: which selected group it falls in (a look-up in
-  // the selection), then the row (through the mapping table if there is one: a second,
-  // dependent look-up).  Positions in the rolling buffer look up position 0 instead and
-  // ignore the result.  The look-ups are unconditional, and the choice between cache and
-  // buffer is only made when the rows are requested, an iteration later: a look-up inside a
-  // branch, or one that depends on another of the same iteration, is waited for on the spot,
-  // together with every key and value load issued before it.
-  struct Rows {
-    uint32_t k, v[4];
-  };
-  auto cache_pos = [&](int ub, int t) {
-    const int tok = position(ub, t);
-    return in_buffer(tok) ? 0 : tok;
-  };
-  auto find_groups = [&](int ub, Rows& r) {  // -> selected group (its index in the cache)
-    r.k = (uint32_t)sel[group_of(cache_pos(ub, c))];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = (uint32_t)sel[group_of(cache_pos(ub, 4 * g + i))];
-  };
-  auto find_rows = [&](int ub, Rows& r) {  // group -> row (in place)
-    auto row = [&](uint32_t grp, int t) {
-      const int tc = cache_pos(ub, t);
-      if constexpr (PAGED) grp = (uint32_t)tab[grp];
-      return grp * (uint32_t)G + (uint32_t)(tc - group_of(tc) * G);
-    };
-    r.k = row(r.k, c);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = row(r.v[i], 4 * g + i);
-  };
-  auto request = [&](int ub, const Rows& r, uint4 (&kv)[4], uint4 (&vv)[4]) {
-    {
-      const int tok = position(ub, c);
-      const uint16_t* base = (in_buffer(tok) ? Kr + (size_t)(tok - n_tok) * D : Kp + (size_t)r.k * D) + 8 * g;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) kv[j] = *reinterpret_cast<const uint4*>(base + 32 * j);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int tok = position(ub, 4 * g + i);
-      vv[i] = *reinterpret_cast<const uint4*>(
-          (in_buffer(tok) ? Vr + (size_t)(tok - n_tok) * D : Vp + (size_t)r.v[i] * D) + 8 * c);
-    }
-  };
-
-  float m = kNegBig, l = 0.f;  // of head c, over the tokens of slice g seen so far (m: of all slices)
-  f32x4_t o[8];
-#pragma unroll
-  for (int bb = 0; bb < 8; ++bb) o[bb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  auto consume = [&](int ub, const uint4 (&kv)[4], const uint4 (&vv)[4]) {
-    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv[j]),
-                                                  __builtin_bit_cast(bf16x8_t, qb[j]), s, 0, 0, 0);
-    // online softmax of head c over tokens 4g .. 4g+3 (logits in log2 units)
-    bool ok[4];
-    float z[4];
-    float mt = kNegBig;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ok[i] = attended(ub, 4 * g + i);
-      z[i] = s[i] * scale_log2e;
-      mt = ok[i] ? fmaxf(mt, z[i]) : mt;
-    }
-    mt = fmaxf(mt, xor_lane<16>(mt));
-    mt = fmaxf(mt, xor_lane<32>(mt));
-    const float mn = fmaxf(m, mt);
-    const float alpha = __builtin_amdgcn_exp2f(m - mn);
-    float pw[4];
-    float ls = l * alpha;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      pw[i] = ok[i] ? __builtin_amdgcn_exp2f(z[i] - mn) : 0.f;
-      ls += pw[i];
-    }
-    l = ls;
-    if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {  // some head's maximum moved: rescale
-#pragma unroll
-      for (int bb = 0; bb < 8; ++bb) o[bb] *= alpha;
-    }
-    m = mn;
-    uint2 pb;  // P^T operand: head c, tokens 4g .. 4g+3
-    pb.x = pack_bf16x2(pw[0], pw[1]);
-    pb.y = pack_bf16x2(pw[2], pw[3]);
-    const uint32_t w[4][4] = {{vv[0].x, vv[0].y, vv[0].z, vv[0].w},
-                              {vv[1].x, vv[1].y, vv[1].z, vv[1].w},
-                              {vv[2].x, vv[2].y, vv[2].z, vv[2].w},
-                              {vv[3].x, vv[3].y, vv[3].z, vv[3].w}};
-#pragma unroll
-    for (int bb = 0; bb < 8; ++bb) {
-      // element bb of the four loaded rows: the low or the high halves of dword bb / 2
-      constexpr uint32_t kLow = 0x05040100u, kHigh = 0x07060302u;  // byte selectors of v_perm_b32
-      const uint32_t selb = (bb & 1) ? kHigh : kLow;
-      uint2 va;
-      va.x = __builtin_amdgcn_perm(w[1][bb / 2], w[0][bb / 2], selb);
-      va.y = __builtin_amdgcn_perm(w[3][bb / 2], w[2][bb / 2], selb);
-      o[bb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, va),
-                                                        __builtin_bit_cast(s16x4_t, pb), o[bb], 0, 0, 0);
-    }
-  };
-
-  const int ub0 = u0 + wave * kAttnUnitsPerWave;
-  // Look-ups run ahead of the tile whose keys and values are being requested: by one tile,
-  // or by two (groups) and one (mapping table) when there is a table.
-  uint4 kv[4], vv[4];
-  Rows rows, ahead;
-  find_groups(ub0, rows);
-  find_rows(ub0, rows);
-  if constexpr (PAGED) find_groups(ub0 + kStep, ahead);
-  KVS_ATTN_TRACE(1);
-  for (int ub = ub0; ub < u1; ub += kStep) {
-    request(ub, rows, kv, vv);
-    if constexpr (PAGED) {
-      rows = ahead;                        // groups of the next tile, found an iteration ago
-      find_rows(ub + kStep, rows);         // (past the end: position 0)
-      find_groups(ub + 2 * kStep, ahead);
-    } else {
-      find_groups(ub + kStep, ahead);
-    }
-    consume(ub, kv, vv);
-    if constexpr (!PAGED) {
-      rows = ahead;
-      find_rows(ub + kStep, rows);
-    }
-  }
-
-  KVS_ATTN_TRACE(2);
-  // ---- this wave's state of head c: add up the four slices' denominators ----------------
-  l += xor_lane<16>(l);
-  l += xor_lane<32>(l);
-  if (c < QPK) {
-    if (g == 0) {
-      ws.m[wave][c] = m;
-      ws.l[wave][c] = l;
-    }
-#pragma unroll
-    for (int bb = 0; bb < 8; ++bb)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) ws.o[wave][AttnWaveStates<D, QPK>::pos(c, 8 * (4 * g + i) + bb)] = o[bb][i];
-  }
-  attn_merge_and_finish<BF16Elem, D, QPK>(ws, part_ml, part_o,
-                                          out + ((size_t)b * n_q_heads + (size_t)k * QPK) * D, arrivals,
-                                          p, split, n_splits);
-  KVS_ATTN_TRACE(6);
+__global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn_mfma_kernel(AttnMfmaArgs a) {
+  __shared__ AttnMfmaShared<QPK, 0> sh;
+  attn_mfma_item<QPK, MODE, INTERLEAVE, 0>(sh, a, blockIdx.y, blockIdx.x);
 }
 
 namespace {
@@ -286,13 +62,11 @@ hipError_t launch_mfma_qpk(const kvs_params& p, const Plan& pl, const void* q, c
   const int units = (p.n_select * p.group_size + rb.len + pl.kv_toks_per_unit - 1) / pl.kv_toks_per_unit;
   const int units_per_split = attn_units_per_split_with_buffer(pl, units);
   const bool interleave = units_per_split >= kAttnInterleaveFromSteps * kAttnUnitsPerWgStep;
-  auto launch = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, grid, block, 0, st, (const S*)q, (const S*)K, (const S*)V, idx, part_ml,
-                       part_o, (S*)out, arrivals, p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows,
-                       p.n_select, G, log2G, recipG, units, units_per_split, pl.attn_splits,
-                       scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len, rb.capacity,
-                       slot_table, pl.n_groups);
-  };
+  const AttnMfmaArgs a{(const S*)q, (const S*)K, (const S*)V, idx, part_ml, part_o, (S*)out, arrivals,
+                       p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows, p.n_select, G, log2G, recipG, units,
+                       units_per_split, pl.attn_splits, scale * kLog2e, (const S*)rb.K, (const S*)rb.V,
+                       rb.len, rb.capacity, slot_table, pl.n_groups};
+  auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, st, a); };
   if (interleave) {
     if (slot_table) launch(attn_mfma_kernel<QPK, kAttnPaged, true>);
     else if (rb.len > 0) launch(attn_mfma_kernel<QPK, kAttnRolling, true>);

@@ -8,6 +8,17 @@ namespace kvs {
 
 constexpr int kWave = 64;
 
+// A pointer to device (global) memory whose address space the compiler can no longer see -
+// because it was read back from a structure in memory - marked as such again: without this
+// every access through it becomes a flat access, which also waits on the LDS counter.
+template <class T>
+__device__ __forceinline__ T* as_global(T* p) {
+  typedef T __attribute__((address_space(1))) * global_ptr;
+  global_ptr g = (global_ptr)p;
+  asm volatile("" : "+s"(g));  // (uniform pointers only; keeps the two casts from cancelling)
+  return (T*)g;
+}
+
 // ---- storage element traits ------------------------------------------------
 // A lane always moves 16 bytes per load: 4 fp32, 8 bf16 or 16 fp8 values.
 struct F32Elem {
@@ -195,6 +206,10 @@ __device__ __forceinline__ float allreduce_lanes(float x) {
 // another workgroup.
 
 __device__ __forceinline__ void publish_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void publish_store(int* p, int v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -21,6 +21,7 @@ constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per C
 constexpr int kAttnWgThreads = KVS_ATTN_THREADS;
 constexpr int kAttnUnitsPerWave = 4;  // (K,V) load pairs a wave keeps in flight (5: no gain, 6: spills)
 constexpr int kAttnUnitsPerWgStep = (kAttnWgThreads / 64) * kAttnUnitsPerWave;
+constexpr int kSelectScorePad = 2304;           // floats of padding behind the workspace's group scores
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 // The matrix-core attention kernel (bf16, d = 128) takes over from this many query heads
 // per KV head on (measured: level with the vector-ALU kernel at 1 and 2, 5 % faster at 3,
@@ -32,6 +33,12 @@ constexpr int kSelectHistBins = 4096;          // per-problem histogram of the t
 constexpr int kAttnMfmaMinHeadsPerKv = KVS_ATTN_MFMA_MIN_QPK;
 constexpr int kAttnMfmaTargetWgs = 256;
 constexpr int kAttnInterleaveFromSteps = 12;   // workgroup steps per split from which the splits are interleaved
+#ifndef KVS_STEP_PREDICT_UNROLL
+#define KVS_STEP_PREDICT_UNROLL 8
+#endif
+constexpr int kStepPredictUnroll = KVS_STEP_PREDICT_UNROLL;  // wave-loads in flight per wave in the single-launch step (16 waves per compute unit)
+constexpr int kStepPredictUnitsPerWgStep = 8 * kStepPredictUnroll;
+constexpr int kStepTargetWgs = 512;            // workgroup slots of the single-launch step on 256 compute units
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
 constexpr int kMetaMfmaTargetWgs = 1024;         // workgroups of the matrix-core metadata kernel
@@ -63,15 +70,30 @@ struct Plan {
   int predict_units;        // wave-loads per problem
   int predict_units_per_wg;
   int predict_chunks;       // workgroups per problem
+  // the same for the single-launch step (its workgroups keep more loads in flight per wave,
+  // so its workgroup step is longer)
+  int step_predict_units_per_wg;
+  int step_predict_chunks;
   // attention
   int kv_lanes_per_tok;     // lanes of 16 B that cover one K (or V) row
   int kv_toks_per_unit;     // tokens covered by one wave-wide load
   int attn_units;           // wave-loads (of K, and as many of V) per problem
   int attn_units_per_split;
   int attn_splits;          // workgroups per problem
-  // workspace layout (byte offsets, 256-byte aligned).  The arrival counters at
-  // off_sync must be zero when a call starts; every call leaves them zero.
+  // the same for the single-launch step, whose attention items share the grid's workgroup
+  // slots with everything else: one item per slot (two per compute unit) where the problems
+  // are long enough, so that the slots stay evenly loaded
+  int step_attn_units_per_split;
+  int step_attn_splits;
+  // workspace layout (byte offsets, 256-byte aligned).  The counter area at off_sync
+  // (sync_bytes long: the counters below, then the score histograms at off_hist) must be zero
+  // when a call starts; every call leaves it zero.
   size_t off_sync, sync_bytes, off_hist, off_gs, off_part_ml, off_part_o, off_qlr, total_bytes;
+  // counters at the start of that area, as int offsets from off_sync: per problem the arrival
+  // counter of the attention splits, the count of finished prediction chunks and the
+  // selection-done flag; then three launch-wide words of the single-launch step (next work
+  // item, workgroups that have left, error)
+  int sync_arrivals, sync_pred_done, sync_sel_done, sync_ticket;
 };
 
 Plan make_plan(const kvs_params& p);
@@ -110,5 +132,18 @@ hipError_t launch_attn_mfma(const kvs_params& p, const Plan& pl, const void* q, 
 hipError_t launch_overlap(const kvs_params& p, const Plan& pl, const int32_t* idx_prev,
                           const int32_t* idx_cur, int32_t* common, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
+
+// The whole step (prediction, selection, attention) as one launch of a persistent grid:
+// whether it covers these parameters, and its launch.  gs: the workspace's score area (the
+// selection items read a little beyond its end, into the padding make_plan leaves there);
+// gs_copy: nullable, the caller's array that receives the scores as well; sync: the counter
+// area of the workspace (zero on entry, left zero).  Same results, bit for bit, as launch_predict + launch_topk + launch_attn.
+bool fused_step_applies(const kvs_params& p, const Plan& pl);
+hipError_t launch_fused_step(const kvs_params& p, const Plan& pl, const void* q, const void* K_lr,
+                             const float* A, const void* K, const void* V, float* gs, float* gs_copy,
+                             int32_t* idx, float* part_ml, float* part_o, void* out, int* sync,
+                             hipStream_t st);
+// Bound of the in-kernel waits of that launch, in polls (<= 0: the default).
+void set_fused_wait_limit(int polls);
 
 }  // namespace kvs

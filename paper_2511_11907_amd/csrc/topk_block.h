@@ -38,24 +38,32 @@ constexpr int kTopkSmallPerLane = 8;  // second instantiation, for problems of a
 constexpr int kTopkChunk = 8;         // register slots handled (and loads in flight) per uniform branch
 constexpr int kTopkBins = 4096;       // histogram over key >> kTopkLowBits
 constexpr int kTopkLowBits = 20;
-constexpr int kTopkBinsPerLane = kTopkBins / kTopkThreads;
-constexpr int kTopkBinsPerWave = kTopkBins / kTopkWaves;
+constexpr int kTopkPublishedPad = 2304;  // floats readable beyond the scores of a PUBLISHED call (> 4 per lane + one chunk)
+constexpr int kTopkSegs = 16;          // the first histogram is searched in 16 segments of 256 bins
+constexpr int kTopkBinsPerSeg = kTopkBins / kTopkSegs;
 constexpr int kTopkListPerLane = 16;  // keys of one bin that step 2's wave takes into registers, per lane
 constexpr int kTopkListCap = kTopkListPerLane * kWave;
 
 constexpr int kTopkLevels = 3;        // histogram levels below the first: 8 + 8 + 4 bits
 constexpr int kTopkLevelBins = 256;
 static_assert(kTopkLowBits == 8 + 8 + 4, "the lower levels must cover the low bits");
-static_assert(kTopkBinsPerLane == 4 && kTopkLevelBins == 4 * kWave, "histograms are read four bins per lane");
-static_assert(kTopkWaves == 16, "the prefix over the waves is taken inside one row of 16 lanes");
+static_assert(kTopkBinsPerSeg == 4 * kWave && kTopkLevelBins == 4 * kWave, "histograms are read four bins per lane");
+static_assert(kTopkWaves <= 16 && kTopkSegs == 16, "prefixes over waves and segments are taken inside one row of 16 lanes");
 
 // Histograms are stored top bin first (bin b at index size-1-b): the search runs from the
 // largest keys downwards, and a lane then reads its four bins as one 16-byte piece.
+constexpr int kTopkStageElems = 8192;  // scores staged through LDS per pass of a PUBLISHED call
+constexpr int kTopkStageWords = kTopkStageElems + kTopkStageElems / 32;  // (one pad word per 32: conflict-free slices)
 struct TopkShared {
-  alignas(16) int hist[kTopkBins];                    // top-12-bit histogram
-  alignas(16) uint32_t list[kTopkListCap];            // keys of the bin that holds the M-th key
-  alignas(16) int sub[kTopkLevels][kTopkLevelBins];   // histograms of the lower levels
-  uint32_t wave_tot[2][kTopkWaves];       // per-wave totals of the two block-wide prefix sums
+  union {
+    struct {
+      alignas(16) int hist[kTopkBins];                    // top-12-bit histogram
+      alignas(16) uint32_t list[kTopkListCap];            // keys of the bin that holds the M-th key
+      alignas(16) int sub[kTopkLevels][kTopkLevelBins];   // histograms of the lower levels
+    };
+    float stage[kTopkStageWords];  // PUBLISHED calls only, before anything above is in use
+  };
+  uint32_t wave_tot[2][kTopkSegs];        // per-segment / per-wave totals of the block-wide prefix sums
   int n_listed;
   int sel_above;                          // hand-over of a level's result and of step 2's
   uint32_t sel_key;
@@ -99,9 +107,9 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
   const uint32_t incl = wave_scan_dpp(v);
   if (lane == kWave - 1) tot[wave] = incl;
   lds_barrier();
-  const int w = lane & (kTopkWaves - 1);
+  const int w = lane & 15;  // (at most 16 waves: the waves before this one all sit in one row)
   const int before = row_scan_dpp(w < wave ? (int)tot[w] : 0);
-  return (uint32_t)__builtin_amdgcn_readlane(before, kTopkWaves - 1) + incl - v;
+  return (uint32_t)__builtin_amdgcn_readlane(before, 15) + incl - v;
 }
 
 // A lane's four bins `b` (top bin first) of a histogram whose bins before this lane's hold
@@ -198,29 +206,43 @@ __device__ __forceinline__ void topk_level_block(uint32_t& prefix, int& above, i
   above = sh.sel_above;
 }
 
-// All kTopkThreads lanes of the workgroup must call this with the same arguments.
+// All THREADS lanes of the workgroup must call this with the same arguments (THREADS = 1024
+// in the selection kernel, 512 in the single-launch decode step).
 // g: NG scores (16-byte aligned if NG is a multiple of 4); out: M indices;
-// 1 <= M <= NG <= kTopkThreads * SLOTS.
+// 1 <= M <= NG <= THREADS * SLOTS.
 // hist_global: nullptr => the histogram of the top 12 key bits is built here, in LDS;
 // otherwise it points at the problem's kTopkBins counters in global memory (bin b at
 // index b), completed by an earlier kernel, and they are reset to zero on the way.
-template <int SLOTS>
+// PUBLISHED: the scores were written by other workgroups of the same launch, and the indices
+// are read by other workgroups of it: both move with device-scope loads and stores.  The
+// scores are then read in whole rounds of THREADS elements, the last one possibly past the
+// end (ignored): g must be readable up to kTopkPublishedPad floats beyond its NG scores.
+template <int SLOTS, int THREADS = kTopkThreads, bool PUBLISHED = false>
 __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__ out, int NG, int M,
                                            int* hist_global, TopkShared& sh) {
   static_assert(SLOTS % kTopkChunk == 0 && SLOTS <= kTopkMaxPerLane, "slots come in whole chunks");
+  constexpr int WAVES = THREADS / kWave;
+  static_assert(WAVES <= 16 && kTopkSegs % WAVES == 0, "every wave searches a whole number of histogram segments");
+  constexpr int SPW = kTopkSegs / WAVES;  // histogram segments per wave
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   // the problem's histogram, if it was accumulated elsewhere: requested first so that
-  // its latency overlaps the loads of the scores.  A lane takes bins 4095-4*tid downwards.
-  int4 mine_raw = make_int4(0, 0, 0, 0);
-  int* const mine_global = hist_global ? hist_global + (kTopkBins - kTopkBinsPerLane * (tid + 1)) : nullptr;
-  if (hist_global) mine_raw = *reinterpret_cast<const int4*>(mine_global);
+  // its latency overlaps the loads of the scores.  Histograms are handled top bin first:
+  // position i stands for bin 4095 - i; a lane takes four consecutive positions of each of
+  // its wave's segments.
+  auto my_pos = [&](int sg) { return kTopkBinsPerSeg * (wave * SPW + sg) + 4 * lane; };
+  int4 mine_raw[SPW];
+#pragma unroll
+  for (int sg = 0; sg < SPW; ++sg) {
+    mine_raw[sg] = make_int4(0, 0, 0, 0);
+    if (hist_global) mine_raw[sg] = *reinterpret_cast<const int4*>(hist_global + (kTopkBins - 4 - my_pos(sg)));
+  }
 
   // A lane owns a contiguous slice of kpt scores (what the ordered compaction needs).
   // With NG a multiple of four the slice is a whole number of 16-byte pieces and is
   // fetched as such: a wave then touches a few cache lines per load instead of 64.
   const bool vec = (NG & 3) == 0;  // uniform
-  int kpt = (NG + kTopkThreads - 1) / kTopkThreads;  // scores per lane
+  int kpt = (NG + THREADS - 1) / THREADS;  // scores per lane
   if (vec) kpt = (kpt + 3) & ~3;
   const int first = tid * kpt;
   const int n_real = max(0, min(kpt, NG - first));  // slots of this lane that hold a score
@@ -234,9 +256,48 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     // every chunk's loads are requested before the first value is looked at, so a long
     // slice still costs one memory latency
     float x[SLOTS];
+    if constexpr (PUBLISHED) {
+      // Fetched with whole-wave contiguous device-scope loads (lane t takes elements t,
+      // t + THREADS, ...: a few memory requests per instruction where slice-wise loads would
+      // make 64, each going all the way to memory), all requested together, and handed to
+      // the lanes' slices through LDS, kTopkStageElems scores per pass.
+      constexpr int kPerPass = kTopkStageElems / THREADS;
+      static_assert(kTopkStageElems % THREADS == 0, "a pass is a whole number of loads per lane");
+      const int nk = (NG + THREADS - 1) / THREADS;  // loads per lane: uniform, <= SLOTS
+      float raw[SLOTS];
+#pragma unroll
+      for (int k = 0; k < SLOTS; ++k) {
+        raw[k] = 0.f;
+        if (k < nk) raw[k] = load_published(g + k * THREADS + tid);  // (uniform; up to THREADS - 1 past the end)
+      }
+#pragma unroll
+      for (int k = 0; k < SLOTS; ++k) asm volatile("" : "+v"(raw[k]));
+#pragma unroll
+      for (int j = 0; j < SLOTS; ++j) x[j] = 0.f;
+#pragma unroll
+      for (int h = 0; h * kPerPass < SLOTS; ++h) {
+        if (h * kPerPass < nk) {  // uniform
+#pragma unroll
+          for (int kk = 0; kk < kPerPass; ++kk) {
+            if (h * kPerPass + kk < SLOTS) {
+              const int e = kk * THREADS + tid;
+              sh.stage[e + (e >> 5)] = raw[h * kPerPass + kk < SLOTS ? h * kPerPass + kk : 0];
+            }
+          }
+          lds_barrier();
+#pragma unroll
+          for (int j = 0; j < SLOTS; ++j) {
+            const int e = first + j - h * kTopkStageElems;
+            if (j < kpt && e >= 0 && e < kTopkStageElems) x[j] = sh.stage[e + (e >> 5)];
+          }
+          lds_barrier();  // (the staging area is reused by the next pass, then by the histograms)
+        }
+      }
+    }
 #pragma unroll
     for (int c0 = 0; c0 < SLOTS; c0 += kTopkChunk) {
-      if (c0 < kpt && vec) {  // uniform
+      if (PUBLISHED) {  // (filled above, through LDS)
+      } else if (c0 < kpt && vec) {  // uniform
 #pragma unroll
         for (int j = c0; j < c0 + kTopkChunk; j += 4) {
           const float4 v = *reinterpret_cast<const float4*>(g + min(first + j, NG - 4));
@@ -278,49 +339,58 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
 
   KVS_TOPK_TRACE(1);
   // ---- 1. histogram of the top 12 bits, and the bin of the M-th key -------------------------
-  for (int i = tid; i < kTopkLevels * kTopkLevelBins; i += kTopkThreads) (&sh.sub[0][0])[i] = 0;
+  for (int i = tid; i < kTopkLevels * kTopkLevelBins; i += THREADS) (&sh.sub[0][0])[i] = 0;
   if (tid == 0) sh.n_listed = 0;  // (both ordered before their use by the barrier of this step)
-  int mine[kTopkBinsPerLane];     // bins 4095-4*tid downwards
+  int mine[SPW][4];               // this lane's bins of each of its wave's segments, top first
   // the histogram built here, in LDS, from the keys in registers (two barriers)
   auto build_here = [&]() __attribute__((always_inline)) {
-    for (int i = tid; i < kTopkBins; i += kTopkThreads) sh.hist[i] = 0;
+    for (int i = tid; i < kTopkBins; i += THREADS) sh.hist[i] = 0;
     lds_barrier();
     slice_keys([&](uint32_t k, int j) __attribute__((always_inline)) {
       if (j < n_real) atomicAdd(&sh.hist[kTopkBins - 1 - (int)(k >> kTopkLowBits)], 1);
     });
     lds_barrier();
-    const int4 v = *reinterpret_cast<const int4*>(&sh.hist[kTopkBinsPerLane * tid]);
-    mine[0] = v.x, mine[1] = v.y, mine[2] = v.z, mine[3] = v.w;
+#pragma unroll
+    for (int sg = 0; sg < SPW; ++sg) {
+      const int4 v = *reinterpret_cast<const int4*>(&sh.hist[my_pos(sg)]);
+      mine[sg][0] = v.x, mine[sg][1] = v.y, mine[sg][2] = v.z, mine[sg][3] = v.w;
+    }
   };
   if (hist_global) {
-    // (keeps the histogram load where it was written, ahead of the score loads, instead of
-    // the compiler sinking it to its first use)
-    asm volatile("" : "+v"(mine_raw.x), "+v"(mine_raw.y), "+v"(mine_raw.z), "+v"(mine_raw.w));
-    mine[0] = mine_raw.w, mine[1] = mine_raw.z, mine[2] = mine_raw.y, mine[3] = mine_raw.x;
-    *reinterpret_cast<int4*>(&sh.hist[kTopkBinsPerLane * tid]) = make_int4(mine[0], mine[1], mine[2], mine[3]);
+#pragma unroll
+    for (int sg = 0; sg < SPW; ++sg) {
+      // (keeps the histogram load where it was written, ahead of the score loads, instead of
+      // the compiler sinking it to its first use)
+      asm volatile("" : "+v"(mine_raw[sg].x), "+v"(mine_raw[sg].y), "+v"(mine_raw[sg].z), "+v"(mine_raw[sg].w));
+      mine[sg][0] = mine_raw[sg].w, mine[sg][1] = mine_raw[sg].z, mine[sg][2] = mine_raw[sg].y, mine[sg][3] = mine_raw[sg].x;
+      *reinterpret_cast<int4*>(&sh.hist[my_pos(sg)]) = make_int4(mine[sg][0], mine[sg][1], mine[sg][2], mine[sg][3]);
+    }
   } else {
     build_here();
   }
   KVS_TOPK_TRACE(2);
   uint32_t prefix;
   int above;  // keys in bins above the one that holds the M-th key
-  // Every wave by itself, after one barrier: which wave's 256 bins hold the M-th key, then
-  // which of those bins.  Returns the number of keys the histogram holds in all.
-  auto locate = [&](uint32_t* wave_tot) __attribute__((always_inline)) {
-    const uint32_t tot = (uint32_t)(mine[0] + mine[1] + mine[2] + mine[3]);
-    const uint32_t incl = wave_scan_dpp(tot);
-    if (lane == kWave - 1) wave_tot[wave] = incl;
+  // Every wave by itself, after one barrier: which segment of 256 bins holds the M-th key,
+  // then which of those bins.  Returns the number of keys the histogram holds in all.
+  auto locate = [&](uint32_t* seg_tot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int sg = 0; sg < SPW; ++sg) {
+      const uint32_t tot = (uint32_t)(mine[sg][0] + mine[sg][1] + mine[sg][2] + mine[sg][3]);
+      const uint32_t incl = wave_scan_dpp(tot);
+      if (lane == kWave - 1) seg_tot[wave * SPW + sg] = incl;
+    }
     lds_barrier();
-    const int w = lane & (kTopkWaves - 1);
-    const int t_w = (int)wave_tot[w];
-    const int upto_w = row_scan_dpp(t_w);  // keys in the bins of waves 0..w
-    const unsigned long long reached = __ballot(upto_w >= M) & ((1ull << kTopkWaves) - 1ull);
-    const int w_sel = reached ? (int)__builtin_ctzll(reached) : kTopkWaves - 1;
+    const int w = lane & (kTopkSegs - 1);
+    const int t_w = (int)seg_tot[w];
+    const int upto_w = row_scan_dpp(t_w);  // keys in the bins of segments 0..w
+    const unsigned long long reached = __ballot(upto_w >= M) & ((1ull << kTopkSegs) - 1ull);
+    const int w_sel = reached ? (int)__builtin_ctzll(reached) : kTopkSegs - 1;
     above = __builtin_amdgcn_readlane(upto_w - t_w, w_sel);
     int in_bin;
-    const int pos = topk_scan_256(&sh.hist[kTopkBinsPerWave * w_sel], lane, M, above, in_bin);
-    prefix = (uint32_t)(kTopkBins - 1 - (kTopkBinsPerWave * w_sel + pos)) << kTopkLowBits;
-    return __builtin_amdgcn_readlane(upto_w, kTopkWaves - 1);
+    const int pos = topk_scan_256(&sh.hist[kTopkBinsPerSeg * w_sel], lane, M, above, in_bin);
+    prefix = (uint32_t)(kTopkBins - 1 - (kTopkBinsPerSeg * w_sel + pos)) << kTopkLowBits;
+    return __builtin_amdgcn_readlane(upto_w, kTopkSegs - 1);
   };
   const int counted = locate(sh.wave_tot[0]);
   if (hist_global && counted != NG) {  // uniform
@@ -433,12 +503,18 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
     const bool gt = k > T, eq = k == T;
     // (the bound only matters with a histogram that does not belong to these scores)
     const int pos = gt_before + min(eq_before, need);
-    if ((gt || (eq && eq_before < need)) && pos < M) out[pos] = first + j;
+    if ((gt || (eq && eq_before < need)) && pos < M) {
+      if constexpr (PUBLISHED) publish_store(&out[pos], first + j);
+      else out[pos] = first + j;
+    }
     gt_before += gt ? 1 : 0;
     eq_before += eq ? 1 : 0;
   });
   if (hist_global) {  // leave the counters zero for the next call
-    if ((mine_raw.x | mine_raw.y | mine_raw.z | mine_raw.w) != 0) *reinterpret_cast<int4*>(mine_global) = make_int4(0, 0, 0, 0);
+#pragma unroll
+    for (int sg = 0; sg < SPW; ++sg)
+      if ((mine_raw[sg].x | mine_raw[sg].y | mine_raw[sg].z | mine_raw[sg].w) != 0)
+        *reinterpret_cast<int4*>(hist_global + (kTopkBins - 4 - my_pos(sg))) = make_int4(0, 0, 0, 0);
   }
 }
 

@@ -288,7 +288,7 @@ def test_uninitialised_histogram_is_noticed_and_cannot_write_out_of_bounds():
     ref = oracle.predict_select(sh, L.q, klr, L.A)
     np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
     hist_words = B * Hk * 4096
-    first = 256 // 4 * -(-(B * Hk * 4) // 256)          # the histograms follow the 256-byte aligned arrival counters
+    first = 256 // 4 * -(-((3 * B * Hk + 4) * 4) // 256)   # the histograms follow the 256-byte aligned counters
     assert int(ws[first:first + hist_words].abs().max()) == 0, "selection left counters behind"
 
 
