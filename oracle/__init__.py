@@ -28,7 +28,7 @@ class _Params(ctypes.Structure):
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32),
         ("reduce", ctypes.c_int32), ("head_mode", ctypes.c_int32), ("ctx_capacity", ctypes.c_int32),
         ("n_threads", ctypes.c_int32), ("meta_scale", ctypes.c_double),
-        ("softmax_scale", ctypes.c_double),
+        ("softmax_scale", ctypes.c_double), ("meta_scales", ctypes.c_void_p),
     ]
 
 
@@ -50,12 +50,21 @@ class Shape:
     head_mode: int = HEADS_SEPARATE
     ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
     meta_scale: float = 0.0    # K_lr is stored divided by this (0: 1)
+    meta_scales: object = None  # optional float64 array, one scale per selection set (overrides meta_scale)
+
+    def __post_init__(self):
+        if self.meta_scales is not None:     # held as a contiguous float64 array: the C struct takes its address
+            a = np.ascontiguousarray(self.meta_scales, dtype=np.float64)
+            if a.shape != self.sets:
+                raise ValueError(f"meta_scales: expected shape {self.sets}, got {a.shape}")
+            self.meta_scales = a
 
     def _c(self) -> _Params:
+        ptr = None if self.meta_scales is None else self.meta_scales.ctypes.data_as(ctypes.c_void_p)
         return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                        self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
                        self.meta_dtype, self.reduce, self.head_mode, self.ctx_capacity,
-                       self.n_threads, self.meta_scale, self.softmax_scale)
+                       self.n_threads, self.meta_scale, self.softmax_scale, ptr)
 
     @property
     def rows(self) -> int:

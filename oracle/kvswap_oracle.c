@@ -85,9 +85,14 @@ static void store_meta(void* base, int dtype, size_t i, double x) {
   else ((uint16_t*)base)[i] = oracle_round_to_bf16(x);
 }
 
-/* The metadata is stored divided by meta_scale (so that it fits the range of a narrow
- * dtype) and multiplied back when it is read. */
-static double meta_scale(const orc_params* p) { return p->meta_scale != 0.0 ? p->meta_scale : 1.0; }
+/* The metadata is stored divided by a scale (so that it fits the range of a narrow dtype)
+ * and multiplied back when it is read (Sec. 3.2: the precision of the compressed K cache
+ * may be traded).  The scale is meta_scale for every selection set, or, if meta_scales is
+ * given, meta_scales[set] with set = b * H_kv + k (set = b in joint mode). */
+static double meta_scale(const orc_params* p, size_t set) {
+  if (p->meta_scales) return p->meta_scales[set];
+  return p->meta_scale != 0.0 ? p->meta_scale : 1.0;
+}
 
 static int params_ok(const orc_params* p) {
   if (!p) return 0;
@@ -100,6 +105,11 @@ static int params_ok(const orc_params* p) {
   if (p->meta_dtype != ORC_F32 && p->meta_dtype != ORC_BF16 && p->meta_dtype != ORC_FP8_E4M3)
     return 0;
   if (!(p->meta_scale >= 0.0) || isinf(p->meta_scale)) return 0;
+  if (p->meta_scales) {
+    const long sets = p->head_mode == ORC_HEADS_JOINT ? p->batch : (long)p->batch * p->n_kv_heads;
+    for (long i = 0; i < sets; ++i)
+      if (!(p->meta_scales[i] > 0.0) || isinf(p->meta_scales[i])) return 0;
+  }
   if (p->head_mode != ORC_HEADS_SEPARATE && p->head_mode != ORC_HEADS_JOINT) return 0;
   if (p->ctx_capacity != 0 && p->ctx_capacity < p->ctx_len) return 0;
   return 1;
@@ -131,7 +141,7 @@ static int build_metadata_joint(const orc_params* p, const void* K, const float*
             acc += load_elem(K, p->kv_dtype, krow + i) * (double)A[((size_t)k * d + i) * r + j];
         }
         if (K_lr_exact) K_lr_exact[orow + j] = acc;
-        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p));
+        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p, (size_t)b));
       }
     }
   }
@@ -162,7 +172,7 @@ int oracle_build_metadata_rows(const orc_params* p, const void* K, const float* 
         for (int i = 0; i < d; ++i)
           acc += load_elem(K, p->kv_dtype, krow + i) * (double)Ak[(size_t)i * r + j];
         if (K_lr_exact) K_lr_exact[orow + j] = acc;
-        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p));
+        store_meta(K_lr, p->meta_dtype, orow + j, acc / meta_scale(p, (size_t)pi));
       }
     }
   }
@@ -261,7 +271,7 @@ static int predict_select_joint(const orc_params* p, const void* q, const void* 
       for (int h = 0; h < Hq; ++h) {
         double acc = 0.0;
         for (int j = 0; j < r; ++j)
-          acc += q_lr[(size_t)h * r + j] * (meta_scale(p) * load_elem(K_lr, p->meta_dtype, row + j));
+          acc += q_lr[(size_t)h * r + j] * (meta_scale(p, (size_t)b) * load_elem(K_lr, p->meta_dtype, row + j));
         tot += acc;
       }
       s[n] = tot;
@@ -317,7 +327,7 @@ int oracle_predict_select(const orc_params* p, const void* q, const void* K_lr,
       for (int hh = 0; hh < qpk; ++hh) {
         double acc = 0.0;
         for (int j = 0; j < r; ++j)
-          acc += q_lr[(size_t)hh * r + j] * (meta_scale(p) * load_elem(K_lr, p->meta_dtype, row + j));
+          acc += q_lr[(size_t)hh * r + j] * (meta_scale(p, (size_t)pi) * load_elem(K_lr, p->meta_dtype, row + j));
         tot += acc;
       }
       s[n] = tot;

@@ -30,7 +30,8 @@
  * Metadata precision (Sec. 3.2: the compressed K cache only ranks tokens, so its precision
  * may be traded for memory): meta_dtype may also be 8-bit floating point (OCP E4M3,
  * uint8 codes), and K_lr is stored as round(K.A / meta_scale) and read back as
- * meta_scale * stored (meta_scale 0 => 1; it applies to every meta_dtype).
+ * meta_scale * stored (meta_scale 0 => 1; it applies to every meta_dtype).  With
+ * meta_scales every selection set (b, kv head; b in joint mode) has a scale of its own.
  * Storage dtypes: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns), 2 = fp8 E4M3 (uint8).  Stored
  * values are widened to fp64 exactly; every sum is an fp64 sum in natural
  * index order.
@@ -81,6 +82,8 @@ typedef struct {
   int32_t n_threads;   /* OpenMP threads over the (b, kv head) problems; <=1: serial */
   double meta_scale;   /* K_lr is stored divided by this; 0 => 1 */
   double softmax_scale; /* 0 => 1/sqrt(d) */
+  const double* meta_scales; /* nullable: one scale per selection set ([B*H_kv], or [B] in
+                                joint mode), positive and finite; overrides meta_scale */
 } orc_params;
 
 /* K_lr = K . A per KV head, or Flatten(K) . A in joint mode (Sec. 3.2), fp64
