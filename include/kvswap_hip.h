@@ -27,7 +27,8 @@
  * precision may be traded for memory): meta_dtype may be fp32, bf16 or the 8-bit float
  * OCP E4M3 (finite-only, largest value 448; one byte per element, which halves the
  * stream of the prediction again).  K_lr is stored as round(K.A / meta_scale), nearest
- * even, saturating for E4M3; scores use meta_scale * stored.
+ * even, saturating for E4M3; scores use meta_scale * stored.  meta_scale is one number for
+ * the whole call, or (meta_scales) one per selection set.
  *
  * Memory: every pointer below is a DEVICE pointer unless it says "host".  All
  * tensors are contiguous and row-major, 16-byte aligned:
@@ -127,6 +128,13 @@ typedef struct {
   int32_t ctx_capacity;  /* rows allocated per (b, kv head) in K and V, and per selection
                             set in K_lr; 0 => ctx_len.  Rows ctx_len .. capacity-1 are room
                             for the groups a decode loop appends and are never read.       */
+  const float* meta_scales; /* NULL, or a DEVICE array with one metadata scale per selection
+                            set - [B, H_kv], or [B] in joint mode - used instead of
+                            meta_scale: heads (or sequences) whose keys differ by orders of
+                            magnitude then each fit a narrow meta_dtype.  Values must be
+                            positive and finite (not checked: the array is device memory);
+                            16-byte alignment is not required.  A per-head calibration
+                            constant is simply repeated for every sequence.               */
 } kvs_params;
 
 /* Bytes of workspace that any of the calls below may need for these params

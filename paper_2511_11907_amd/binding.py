@@ -45,6 +45,7 @@ class _CParams(ctypes.Structure):
         ("kv_dtype", ctypes.c_int32), ("meta_dtype", ctypes.c_int32), ("reduce", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float), ("head_mode", ctypes.c_int32),
         ("meta_scale", ctypes.c_float), ("ctx_capacity", ctypes.c_int32),
+        ("meta_scales", ctypes.c_void_p),
     ]
 
 
@@ -65,12 +66,20 @@ class Params:
     head_mode: int = KVS_HEADS_SEPARATE
     ctx_capacity: int = 0      # rows allocated per problem in K, V, K_lr (0: ctx_len)
     meta_scale: float = 0.0    # K_lr is stored divided by this (0: 1)
+    meta_scales: object = None  # optional fp32 GPU tensor of shape `sets`: one scale per selection set
 
     def _c(self) -> _CParams:
+        ptr = None
+        if self.meta_scales is not None:
+            t = self.meta_scales
+            import torch
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == self.sets):
+                raise ValueError(f"meta_scales must be a contiguous fp32 GPU tensor of shape {self.sets}")
+            ptr = ctypes.c_void_p(t.data_ptr())
         return _CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.rank,
                         self.ctx_len, self.group_size, self.n_select, self.kv_dtype,
                         self.meta_dtype, self.reduce, self.softmax_scale, self.head_mode,
-                        self.meta_scale, self.ctx_capacity)
+                        self.meta_scale, self.ctx_capacity, ptr)
 
     @property
     def rows(self) -> int:

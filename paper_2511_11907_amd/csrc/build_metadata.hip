@@ -28,8 +28,9 @@ template <typename EK, typename EM, int RC>  // RC = r / 4 output columns per la
 __global__ __launch_bounds__(kMetaThreads) void build_metadata_kernel(
     const typename EK::storage* __restrict__ K, const float* __restrict__ A,
     typename EM::storage* __restrict__ K_lr, int n_kv_heads, int heads_per_set, int ctx_rows,
-    int first_row, int row_end, int d, float meta_scale) {
+    int first_row, int row_end, int d, float meta_scale_all, const float* __restrict__ meta_scales) {
   constexpr int R = RC * 4;
+  const float meta_scale = meta_scales ? meta_scales[blockIdx.y] : meta_scale_all;  // one per selection set
   extern __shared__ float s_k[];  // [kMetaRows][d + 1]
   const int tid = threadIdx.x;
   const int set = blockIdx.y;  // (b, k), or b alone when the heads are projected jointly
@@ -123,7 +124,8 @@ template <typename EM, int D, int MB>  // MB blocks of 16 rank columns (r <= 16 
 __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
     const uint16_t* __restrict__ K, const float* __restrict__ A,
     typename EM::storage* __restrict__ K_lr, int n_kv_heads, int ctx_rows, int first_row,
-    int row_end, int r, int col0, int cols, float meta_scale) {
+    int row_end, int r, int col0, int cols, float meta_scale_all, const float* __restrict__ meta_scales) {
+  const float meta_scale = meta_scales ? meta_scales[blockIdx.y] : meta_scale_all;  // one per selection set
   // this launch produces rank columns col0 .. col0 + cols - 1 (cols <= 16 * MB) of the r
   constexpr int KS = D / 32;  // contraction steps
   constexpr int TB = kMfmaTokenBlocks;
@@ -316,7 +318,8 @@ template <typename EM, int D, int MB>
 __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_joint_kernel(
     const uint16_t* __restrict__ K, const float* __restrict__ A,
     typename EM::storage* __restrict__ K_lr, int n_kv_heads, int ctx_rows, int first_row,
-    int row_end, int r, int col0, int cols, float meta_scale) {
+    int row_end, int r, int col0, int cols, float meta_scale_all, const float* __restrict__ meta_scales) {
+  const float meta_scale = meta_scales ? meta_scales[blockIdx.y] : meta_scale_all;  // one per selection set
   constexpr int KS = D / 32;
   constexpr int TB = kMfmaJointTokenBlocks;
   __shared__ uint4 s_a[3][MB][KS][kWave];
@@ -423,7 +426,7 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* K, const 
   hipLaunchKernelGGL((build_metadata_kernel<EK, EM, RC>), grid, block, lds, st,
                      (const typename EK::storage*)K, A, (typename EM::storage*)K_lr, p.n_kv_heads,
                      pl.kv_heads_per_set, pl.ctx_rows, first_row, first_row + n_rows, p.head_dim,
-                     p.meta_scale != 0.f ? p.meta_scale : 1.0f);
+                     p.meta_scale != 0.f ? p.meta_scale : 1.0f, p.meta_scales);
   return hipGetLastError();
 }
 
@@ -458,7 +461,7 @@ hipError_t launch_build_metadata(const kvs_params& p, const Plan& pl, const void
       for (int col0 = 0; col0 < p.rank; col0 += 64) {
         const int cols = p.rank - col0 < 64 ? p.rank - col0 : 64;
         hipLaunchKernelGGL(kernel, grid, block, 0, st, (const uint16_t*)K, A, out, p.n_kv_heads,
-                           pl.ctx_rows, first_row, first_row + n_rows, p.rank, col0, cols, scale);
+                           pl.ctx_rows, first_row, first_row + n_rows, p.rank, col0, cols, scale, p.meta_scales);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
       }

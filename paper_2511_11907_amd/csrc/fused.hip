@@ -324,7 +324,7 @@ hipError_t launch_fused_step(const kvs_params& p, const Plan& pl, const void* q,
   const float mscale = p.meta_scale != 0.f ? p.meta_scale : 1.0f;
   const PredictArgs pa{q, (int)(p.kv_dtype == KVS_BF16), K_lr, A, gs, gs_copy, p.n_kv_heads, pl.q_per_kv, p.head_dim,
                        pl.n_groups, p.group_size, pl.ctx_rows, pl.predict_units, pl.step_predict_units_per_wg,
-                       (int)(p.reduce == KVS_REDUCE_MEAN), nullptr, nullptr, mscale};
+                       (int)(p.reduce == KVS_REDUCE_MEAN), nullptr, nullptr, mscale, p.meta_scales};
   const int G = p.group_size;
   int log2G = 0;
   while ((1 << log2G) < G) ++log2G;

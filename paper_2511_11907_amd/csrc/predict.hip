@@ -97,7 +97,8 @@ hipError_t launch_one(const kvs_params& p, const Plan& pl, const void* q, const 
     if (e != hipSuccess) return e;
   }
   PredictArgs a{q, q_bf16, K_lr, A, gs, nullptr, p.n_kv_heads, pl.q_per_kv, p.head_dim, pl.n_groups, p.group_size,
-                pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean, hist, (const float*)qlr, scale};
+                pl.ctx_rows, pl.predict_units, pl.predict_units_per_wg, mean, hist, (const float*)qlr, scale,
+                p.meta_scales};
   if (hist) hipLaunchKernelGGL((predict_kernel<E, R, G, true, PAD>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((predict_kernel<E, R, G, false, PAD>), grid, block, 0, st, a);
   return hipGetLastError();

@@ -61,6 +61,7 @@ struct PredictArgs {
   int* hist;
   const float* qlr;
   float meta_scale;
+  const float* meta_scales;  // nullable: one scale per selection set, instead of meta_scale
 };
 
 // Chunk `chunk` of problem `p`, by all kPredictThreads lanes of the workgroup.  PUBLISH: the
@@ -90,7 +91,7 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
             mean = a.mean;
   int* hist = as_global(a.hist);
   const float* qlr = as_global(a.qlr);
-  const float meta_scale = a.meta_scale;
+  const float meta_scale = a.meta_scales ? as_global(a.meta_scales)[p] : a.meta_scale;  // uniform
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wave = tid / kWave;

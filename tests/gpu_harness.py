@@ -127,15 +127,21 @@ def out_values(t: torch.Tensor) -> np.ndarray:
 
 # ---- one full comparison of a small configuration --------------------------------------
 def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bool = True,
-                    meta: str = None, meta_scale: float = 0.0):
+                    meta: str = None, meta_scale: float = 0.0, meta_scales: np.ndarray = None):
     """Whole path at a size the oracle finishes in seconds: metadata, prediction and
     selection, attention with the oracle's indices, and the fused decode step.
-    `meta` overrides the metadata dtype ("f32", "bf16", "fp8")."""
+    `meta` overrides the metadata dtype ("f32", "bf16", "fp8"); `meta_scales` (one per
+    selection set) overrides `meta_scale`."""
     L = make_layer(cfg, layer)
     D = DeviceLayer(L)
     meta = meta or cfg.dtype
     p = kv_params(cfg, reduce=reduce, meta_dtype=meta, meta_scale=meta_scale)
     sh = orc_shape(cfg, reduce=reduce, meta_dtype=meta, meta_scale=meta_scale)
+    if meta_scales is not None:
+        p.meta_scales = torch.from_numpy(np.ascontiguousarray(meta_scales, dtype=np.float32)).to(DEV)
+        # (the oracle gets exactly the fp32 values the library reads)
+        sh = orc_shape(cfg, reduce=reduce, meta_dtype=meta,
+                       meta_scales=np.ascontiguousarray(meta_scales, dtype=np.float32).astype(np.float64))
     B, Hk, N, r, M = cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank, cfg.n_select
     stats = {}
 
@@ -150,6 +156,8 @@ def run_and_compare(cfg: Config, reduce: int = 0, layer: int = 0, check_meta: bo
                            np.abs(storage_to_f32(L.K)).astype(np.float64), np.abs(L.A).astype(np.float64))
         terms = cfg.head_dim * (Hk if cfg.joint else 1)
         sc = meta_scale or 1.0        # stored units: K.A / meta_scale
+        if meta_scales is not None:
+            sc = np.ascontiguousarray(meta_scales, dtype=np.float32).astype(np.float64)[..., None, None]
         stats["meta_mismatch"] = compare_metadata(to_host_storage(klr_gpu), klr_ref, klr_exact / sc,
                                                   absdot / sc, terms, meta)
 

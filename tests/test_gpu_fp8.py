@@ -73,3 +73,39 @@ def test_c4_full_size_fp8_sampled():
 def test_fp8_is_refused_for_keys_and_values():
     p = H.kv_params(PRESETS["c2"], kv_dtype=kv.KVS_FP8_E4M3)
     assert kv.kvs_check_params(p) == 3
+
+
+# ---- one metadata scale per selection set ----------------------------------------------------
+@pytest.mark.parametrize("meta", ["fp8", "bf16", "f32"])
+@pytest.mark.parametrize("joint", [False, True])
+def test_a_scale_per_selection_set(meta, joint):
+    """kvs_params.meta_scales: every (sequence, KV head) - every sequence in joint mode -
+    stores its K_lr divided by its own scale; metadata build, prediction, selection and the
+    whole step against the oracle with the same fp32 scales."""
+    cfg = PRESETS["c2"].replace(name=f"scales_{meta}_{'joint' if joint else 'sep'}", batch=3, ctx_len=4096,
+                                n_select=103, joint=joint)
+    rng = np.random.default_rng(17)
+    sets = (cfg.batch,) if joint else (cfg.batch, cfg.n_kv_heads)
+    scales = np.exp(rng.uniform(np.log(0.05), np.log(2.0), size=sets)).astype(np.float32)
+    _say(cfg.name, H.run_and_compare(cfg, meta=meta, meta_scales=scales))
+
+
+def test_a_uniform_scale_array_gives_the_bits_of_the_scalar():
+    cfg = PRESETS["c2"].replace(name="scales_uniform", batch=2, ctx_len=4096, n_select=103)
+    from workloads import make_layer
+    L = make_layer(cfg)
+    D = H.DeviceLayer(L)
+    a = H.kv_params(cfg, meta_dtype="fp8", meta_scale=0.125)
+    b = H.kv_params(cfg, meta_dtype="fp8")
+    b.meta_scales = torch.full((cfg.batch, cfg.n_kv_heads), 0.125, dtype=torch.float32, device=H.DEV)
+    out = []
+    for p in (a, b):
+        klr = torch.empty((cfg.batch, cfg.n_kv_heads, cfg.ctx_len, cfg.rank), dtype=torch.float8_e4m3fn, device=H.DEV)
+        kv.kvs_build_metadata(p, D.K, D.A, klr)
+        idx = torch.empty((cfg.batch, cfg.n_kv_heads, cfg.n_select), dtype=torch.int32, device=H.DEV)
+        gs = torch.empty((cfg.batch, cfg.n_kv_heads, cfg.n_groups), dtype=torch.float32, device=H.DEV)
+        kv.kvs_predict_select(p, D.q, klr, D.A, idx, gs, H.workspace(p))
+        torch.cuda.synchronize()
+        out.append((klr.view(torch.uint8).clone(), idx.clone(), gs.clone()))
+    for x, y in zip(*out):
+        assert torch.equal(x, y)
