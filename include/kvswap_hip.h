@@ -202,7 +202,8 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
  * selection then builds its own score histogram (joint mode: kvs_predict_scores
  * needs the workspace, KVS_ERR_WORKSPACE without).
  * Contract of a non-NULL workspace: if kvs_predict_scores is given a workspace it also
- * leaves the per-problem score histograms there, and the NEXT call on that workspace
+ * leaves the per-problem score histograms there (for up to 32 selection sets; beyond that
+ * the selection is faster building its own), and the NEXT call on that workspace
  * must be kvs_select_topk with the same workspace, params and group_scores (it consumes
  * the histograms and zeroes them again).  Conversely, a workspace passed to
  * kvs_select_topk is expected to hold the histograms of exactly these group_scores.
@@ -307,7 +308,7 @@ kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_
  * that zeroes the counter area, then the launches of kvs_decode_step, on `stream`.  Params
  * whose kvs_workspace_bytes() exceeds KVS_STATIC_SCRATCH_BYTES are refused with
  * KVS_ERR_SCRATCH before anything is launched (every workload of the evaluation fits: the
- * largest, 128 problems of 4096 groups, needs 4.6 MiB).  The device that `stream` belongs to
+ * largest, 128 problems of 4096 groups, needs 5.1 MiB).  The device that `stream` belongs to
  * must be the current device.  On the first call per device the library looks up that
  * device's address of the array; make that first call outside a graph capture.
  * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU

@@ -162,6 +162,13 @@ kvs_status check_rb(const void* rb_K, const void* rb_V, int32_t rb_len, int32_t 
   return KVS_OK;
 }
 
+// The score histograms in the workspace, if prediction and selection hand them over for
+// this many selection sets (both sides decide by this one rule), else nullptr.
+int* hist_handed_over(const Plan& pl, void* workspace) {
+  if (pl.sets > kHistHandOverMaxSets) return nullptr;
+  return (int*)((char*)workspace + pl.off_hist);
+}
+
 kvs_status check_workspace(const Plan& pl, const void* ws, size_t bytes) {
   if (!ws || misaligned(ws) || bytes < pl.total_bytes) return KVS_ERR_WORKSPACE;
   return KVS_OK;
@@ -274,7 +281,7 @@ kvs_status kvs_predict_select(const kvs_params* p, const void* q, const void* K_
   if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
   float* gs = group_scores ? group_scores : (float*)((char*)workspace + pl.off_gs);
   hipStream_t st = (hipStream_t)stream;
-  int* hist = (int*)((char*)workspace + pl.off_hist);
+  int* hist = hist_handed_over(pl, workspace);
   float* qlr = pl.kv_heads_per_set > 1 ? (float*)((char*)workspace + pl.off_qlr) : nullptr;
   if ((s = dev(launch_predict(*p, pl, q, K_lr, A, gs, hist, qlr, st))) != KVS_OK) return s;
   return dev(launch_topk(*p, pl, gs, idx, hist, st));
@@ -294,7 +301,7 @@ kvs_status kvs_predict_scores(const kvs_params* p, const void* q, const void* K_
   if (!workspace && pl.kv_heads_per_set > 1) return KVS_ERR_WORKSPACE;  // holds the low-rank queries
   if (workspace) {
     if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
-    hist = (int*)((char*)workspace + pl.off_hist);
+    hist = hist_handed_over(pl, workspace);
     if (pl.kv_heads_per_set > 1) qlr = (float*)((char*)workspace + pl.off_qlr);
   }
   return dev(launch_predict(*p, pl, q, K_lr, A, group_scores, hist, qlr, (hipStream_t)stream));
@@ -310,7 +317,7 @@ kvs_status kvs_select_topk(const kvs_params* p, const float* group_scores, int32
   int* hist = nullptr;
   if (workspace) {
     if ((s = check_workspace(pl, workspace, workspace_bytes)) != KVS_OK) return s;
-    hist = (int*)((char*)workspace + pl.off_hist);
+    hist = hist_handed_over(pl, workspace);
   }
   return dev(launch_topk(*p, pl, group_scores, idx, hist, (hipStream_t)stream));
 }

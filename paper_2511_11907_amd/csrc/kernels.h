@@ -22,6 +22,11 @@ constexpr int kAttnWgThreads = KVS_ATTN_THREADS;
 constexpr int kAttnUnitsPerWave = 4;  // (K,V) load pairs a wave keeps in flight (5: no gain, 6: spills)
 constexpr int kAttnUnitsPerWgStep = (kAttnWgThreads / 64) * kAttnUnitsPerWave;
 constexpr int kSelectScorePad = 2304;           // floats of padding behind the workspace's group scores
+// Up to this many selection sets the prediction kernel also accumulates the sets' score
+// histograms for the selection kernel (measured: with 8 sets the selection is 0.2 us shorter for it,
+// with 32 it makes no difference, with 64 or 128 the prediction kernel's extra atomics cost
+// 1 us more than the selection saves).
+constexpr int kHistHandOverMaxSets = 32;
 constexpr int kSelectHistBins = 4096;          // per-problem histogram of the top 12 key bits
 // The matrix-core attention kernel (bf16, d = 128) takes over from this many query heads
 // per KV head on (measured: level with the vector-ALU kernel at 1 and 2, 5 % faster at 3,

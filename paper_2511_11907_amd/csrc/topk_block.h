@@ -444,11 +444,14 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
         for (int c = 0; c < kTopkListPerLane; ++c)
           if (c * kWave < n_listed) f(lk[c], c * kWave + lane < n_listed);  // uniform
       };
+      KVS_TOPK_TRACE(7);
       // As soon as the bin found holds a single key, that key is T.
       int settled = kTopkLevelShift[0];  // bits of `prefix` below this one are still open
       topk_level_count<0, false>(prefix, sh, listed_keys);
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      KVS_TOPK_TRACE(8);
       int in_bin = topk_level_scan<0>(prefix, above, M, sh);
+      KVS_TOPK_TRACE(9);
       if (in_bin != 1) {  // uniform
         settled = kTopkLevelShift[1];
         topk_level_count<1, false>(prefix, sh, listed_keys);
@@ -468,6 +471,7 @@ __device__ __forceinline__ void topk_block(const float* g, int32_t* __restrict__
           if (is != 0ull) prefix = (uint32_t)__builtin_amdgcn_readlane((int)k, (int)__builtin_ctzll(is));
         });
       }
+      KVS_TOPK_TRACE(10);
       if (lane == 0) sh.sel_key = prefix, sh.sel_above = above;
     }
     lds_barrier();
