@@ -3,7 +3,7 @@
 // KV head) problems run as work items of one persistent grid instead of three dependent
 // launches.
 //
-// Why: the three phases of one problem depend on each other, but the problems do not.  As
+// The idea: the three phases of one problem depend on each other, but the problems do not.  As
 // three launches every phase waits for the slowest workgroup of the previous one, the
 // latency-bound selection (5 us of dependent steps on a few KiB) sits between the two
 // streaming kernels with the memory system idle, and each launch pays its own ramp-up and
@@ -25,9 +25,16 @@
 // leaves.
 //
 // Which workgroup runs which item depends on timing; what an item computes does not: scores
-// and indices are functions of the inputs alone, every attention split sums a fixed set of
-// tokens in a fixed order and the splits are merged in index order, so outputs are
-// reproducible bit for bit and equal to those of the three separate launches.
+// and indices are functions of the inputs alone and equal those of the three separate
+// launches bit for bit; every attention split sums a fixed set of tokens in a fixed order
+// and the splits are merged in index order, so the outputs are reproducible bit for bit.
+// They differ from the three launches' outputs in the last fp32 roundings only, because this
+// launch cuts a problem's selected tokens into its own number of splits.
+//
+// Measured on an MI355X this form is slower than the three launches at every benchmark
+// shape (a memory round trip takes several times longer inside a grid that saturates the
+// memory system, and the selection is a chain of such round trips), so the library's default
+// step keeps the three launches and this launch is an entry point of its own.
 //
 // Values that cross workgroups inside the launch (group scores, selected indices, split
 // partial results, counters) move with device-scope stores and loads (see device_utils.h);
