@@ -114,6 +114,30 @@ __device__ __forceinline__ void swap_odd_even_rows(uint32_t& a, uint32_t& b) {
   a = r[0], b = r[1];
 }
 
+// 16-byte accesses of the streaming operands.  With two rank blocks per pass (r = 32) the
+// kernel is faster with non-temporal keys and results (7-11 % at 16K-128K contexts); with one
+// block it makes no difference and with four (r = 64, r = 128) it is 5-8 % slower, so the
+// hint follows the instantiation.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_keys16(const void* p) {
+  if constexpr (STREAM) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  } else {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+}
+template <bool STREAM>
+__device__ __forceinline__ void store_rows16(void* p, uint4 v) {
+  if constexpr (STREAM) {
+    const u32x4_t w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(p));
+  } else {
+    *reinterpret_cast<uint4*>(p) = v;
+  }
+}
+
 constexpr int kMfmaThreads = 256;
 constexpr int kMfmaWaves = kMfmaThreads / kWave;
 constexpr int kMfmaTokenBlocks = 2;                         // blocks of 16 tokens per wave
@@ -173,7 +197,7 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
       const int row = min(row_of(tile, tb), row_end - 1);  // rows past the end are computed and dropped
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        kr[tb][ks] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * D + ks * 32);
+        kr[tb][ks] = load_keys16<MB == 2>(Kp + (size_t)row * D + ks * 32);
     }
   };
 
@@ -242,8 +266,8 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_kernel(
             swap_odd_even_rows(lo[0], lo[1]), swap_odd_even_rows(hi[0], hi[1]);
             // lane group kq now holds ranks (kq & 1) * 16 + (kq & 2) * 4 .. + 7 of its token
             if (row < row_end)
-              *reinterpret_cast<uint4*>(Op + (size_t)row * r + col0 + (kq & 1) * 16 + (kq & 2) * 4) =
-                  make_uint4(lo[0], hi[0], lo[1], hi[1]);
+              store_rows16<true>(Op + (size_t)row * r + col0 + (kq & 1) * 16 + (kq & 2) * 4,
+                                 make_uint4(lo[0], hi[0], lo[1], hi[1]));
           }
           continue;
         }

@@ -46,7 +46,7 @@ constexpr int kStepPredictUnitsPerWgStep = 8 * kStepPredictUnroll;
 constexpr int kStepTargetWgs = 512;            // workgroup slots of the single-launch step on 256 compute units
 constexpr int kAttnTargetWgs = 512;            // measured best: fewer, longer splits (less merge traffic)
 constexpr int kAttnMaxSplitsPerProblem = 256;   // the merge keeps one weight per split in LDS
-constexpr int kMetaMfmaTargetWgs = 1024;         // workgroups of the matrix-core metadata kernel
+constexpr int kMetaMfmaTargetWgs = 512;          // workgroups of the matrix-core metadata kernel: two per compute unit (measured best)
 constexpr int kJointMaxFlatDim = 4096;          // H_kv * d the query projection kernel stages in LDS
 
 // Launch geometry derived from the params alone (the host computes it once per
