@@ -165,10 +165,10 @@ __global__ __launch_bounds__(kAttnThreads, (attn_min_waves<E, QPK, MODE>())) voi
     }
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u)
-      kv[u] = *reinterpret_cast<const uint4*>((RB && rbf[u] ? Kr : Kp) + off[u]);
+      kv[u] = load16<true>((RB && rbf[u] ? Kr : Kp) + off[u]);  // read once: non-temporal
 #pragma unroll
     for (int u = 0; u < kAttnUnroll; ++u)
-      vv[u] = *reinterpret_cast<const uint4*>((RB && rbf[u] ? Vr : Vp) + off[u]);
+      vv[u] = load16<true>((RB && rbf[u] ? Vr : Vp) + off[u]);
   };
   // consume(ub, kv, vv): online-softmax update with the batch that starts at unit ub
   auto consume = [&](int ub, const uint4 (&kv)[kAttnUnroll], const uint4 (&vv)[kAttnUnroll]) {

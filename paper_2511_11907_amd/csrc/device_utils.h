@@ -240,4 +240,16 @@ __device__ __forceinline__ void publish_complete_and_barrier() {
 // emitted; the hardware returns the loads of a wave in order).
 __device__ __forceinline__ void consume_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 
+// A 16-byte global load, optionally with the non-temporal hint (data that is read once).
+typedef uint32_t kvs_u32x4 __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ uint4 load16(const void* p) {
+  if constexpr (STREAM) {
+    const kvs_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const kvs_u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  } else {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+}
+
 }  // namespace kvs
