@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kMfmaThreads) void build_metadata_mfma_joint_kernel
         const int row = min(row0 + tb * 16, row_end - 1);  // rows past the end are computed and dropped
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          kr[tb][ks] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * D + ks * 32);
+          kr[tb][ks] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * D + ks * 32);  // (non-temporal: slower here)
       }
       lds_barrier();  // everyone is done with the previous head's block
       {

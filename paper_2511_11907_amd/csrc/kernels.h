@@ -11,8 +11,8 @@ namespace kvs {
 
 // Work granules of the streaming kernels (units = wave-wide 1 KiB loads).
 constexpr int kPredictWgThreads = 512;
-constexpr int kPredictUnitsPerWgStep = 8 * 8;  // 8 waves x 8 loads in flight
-constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per CU (three fit at once); measured flat from 512 to 2048
+constexpr int kPredictUnitsPerWgStep = 8 * 4;  // 8 waves x 4 loads in flight (54-62 registers: all four workgroups of a CU resident)
+constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per CU; measured flat from 512 to 2048
 // (512-lane attention workgroups: in one run, same 512-workgroup grid, 256 -> 512 lanes took
 // c4 from 64.8 to 58.6 us and c2 from 16.1 to 13.5 us, c3 unchanged)
 #ifndef KVS_ATTN_THREADS

@@ -23,8 +23,8 @@ constexpr int kPredictUnroll = kPredictUnitsPerWgStep / kPredictWaves;  // wave-
 static_assert(kPredictUnroll * kPredictWaves == kPredictUnitsPerWgStep, "granule mismatch");
 
 // Geometry of one instantiation: E metadata element, R rank, G row slots per group, UNROLL
-// wave-wide loads a wave keeps in flight (8 in the prediction kernel, whose 75 registers let
-// three workgroups share a compute unit; more where fewer waves are resident).
+// wave-wide loads a wave keeps in flight (4 in the prediction kernel, whose 54-62 registers
+// let four workgroups share a compute unit; more where fewer waves are resident).
 template <typename E, int R, int G, int UNROLL = kPredictUnroll>
 struct PredictGeom {
   static constexpr int EPL = E::kPerLane;
