@@ -44,8 +44,8 @@ Plan make_plan(const kvs_params& p) {
   pl.n_groups = p.ctx_len / p.group_size;
   pl.q_per_kv = p.n_q_heads / p.n_kv_heads;
 
-  // predict: about four workgroups per compute unit over the whole chip, each streaming at
-  // least one full step of its eight waves
+  // predict: two workgroups per compute unit over the whole chip, each streaming at
+  // least one full step of its waves
   const int meta_epl = p.meta_dtype == KVS_FP8_E4M3 ? 16 : (p.meta_dtype == KVS_BF16 ? 8 : 4);
   pl.meta_lanes_per_row = p.rank / meta_epl;
   pl.meta_rows_per_unit = 64 / pl.meta_lanes_per_row;

@@ -38,10 +38,28 @@ namespace kvs {
 // compute unit; the mapping table's extra look-ahead does not, and a spilled register is
 // reloaded in order behind the key loads, i.e. stalls the value loads for a full latency,
 // so that mode takes what it needs)
+// Start and end time of every workgroup for the debugging harness (compiled only with
+// -DKVS_WG_TRACE_BUILD): two words per workgroup, in launch order.
+#ifdef KVS_WG_TRACE_BUILD
+static __device__ long long g_attn_wg_trace[2 * 8192];
+extern "C" int kvs_debug_attn_wg_trace(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_wg_trace), sizeof(long long) * (size_t)n);
+}
+#define KVS_WG_TRACE(i)                                                                     \
+  do {                                                                                      \
+    const int wg_ = blockIdx.y * gridDim.x + blockIdx.x;                                    \
+    if (threadIdx.x == 0 && wg_ < 8192) g_attn_wg_trace[2 * wg_ + (i)] = wall_clock64();    \
+  } while (0)
+#else
+#define KVS_WG_TRACE(i)
+#endif
+
 template <int QPK, int MODE, bool INTERLEAVE>
 __global__ __launch_bounds__(kAttnThreads, MODE == kAttnPaged ? 2 : 4) void attn_mfma_kernel(AttnMfmaArgs a) {
   __shared__ AttnMfmaShared<QPK, 0> sh;
+  KVS_WG_TRACE(0);
   attn_mfma_item<QPK, MODE, INTERLEAVE, 0>(sh, a, blockIdx.y, blockIdx.x);
+  KVS_WG_TRACE(1);
 }
 
 namespace {

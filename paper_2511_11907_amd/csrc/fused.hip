@@ -80,7 +80,7 @@ extern "C" int kvs_debug_fused_trace(long long* host, int n) {
 namespace kvs {
 
 constexpr int kFusedThreads = 512;
-static_assert(kFusedThreads == kPredictThreads && kFusedThreads == kAttnThreads, "one workgroup size for all items");
+static_assert(kFusedThreads == kStepPredictThreads && kFusedThreads == kAttnThreads, "one workgroup size for all items");
 constexpr int kFusedSelCap = 4096;        // selected groups per problem the attention items hold in LDS
 constexpr int kFusedMaxGroups = kFusedThreads * kTopkMaxPerLane;  // 16384 scores per problem
 constexpr int kFusedWgsPerCu = 2;         // 128 registers per lane, < 80 KiB of LDS
@@ -172,8 +172,8 @@ __device__ __noinline__ void predict_work(ArgSegment seg, int p_in, int chunk_in
   const int p = uniform(p_in), chunk = uniform(chunk_in);
   KVS_PREDICT_TRACE(0);
   const PredictArgs pa = KVS_STEP_ARGS(seg, predict);
-  predict_item<E, R, G, false, PAD, true, kStepPredictUnroll>(
-      lds_block<PredictShared<E, R, G, false, kStepPredictUnroll>>(lds), pa, p, chunk);
+  predict_item<E, R, G, false, PAD, true, kStepPredictUnroll, kFusedThreads>(
+      lds_block<PredictShared<E, R, G, false, kStepPredictUnroll, kFusedThreads>>(lds), pa, p, chunk);
   publish_complete_and_barrier();  // the scores are out before the chunk is counted
   KVS_PREDICT_TRACE(4);
   if (threadIdx.x == 0) atomicAdd(as_global(KVS_STEP_ARGS(seg, fused).pred_done) + p, 1);
@@ -215,7 +215,7 @@ __device__ __noinline__ void attend_work(ArgSegment seg, int p_in, int split_in,
 template <typename E, int R, int G, bool PAD, int QPK, bool INTERLEAVE>
 __global__ __launch_bounds__(kFusedThreads, 4) void decode_step_kernel(StepArgs all_args) {
   union Shared {
-    PredictShared<E, R, G, false, kStepPredictUnroll> predict;
+    PredictShared<E, R, G, false, kStepPredictUnroll, kFusedThreads> predict;
     TopkShared topk;
     AttnMfmaShared<QPK, kFusedSelCap> attn;
   };

@@ -10,9 +10,12 @@
 namespace kvs {
 
 // Work granules of the streaming kernels (units = wave-wide 1 KiB loads).
-constexpr int kPredictWgThreads = 512;
-constexpr int kPredictUnitsPerWgStep = 8 * 4;  // 8 waves x 4 loads in flight (54-62 registers: all four workgroups of a CU resident)
-constexpr int kPredictTargetWgs = 1024;        // four 512-lane workgroups per CU; measured flat from 512 to 2048
+// (prediction: 1024-lane workgroups whose 16 waves share the workgroup's rows dynamically,
+// two per compute unit, four loads in flight per wave: at the 128K workload 79.9 us against
+// 85.4 us for four 512-lane workgroups per compute unit with a fixed split over the waves)
+constexpr int kPredictWgThreads = 1024;
+constexpr int kPredictUnitsPerWgStep = (kPredictWgThreads / 64) * 4;  // 16 waves x 4 loads in flight (54-64 registers: two workgroups per CU)
+constexpr int kPredictTargetWgs = 512;         // two 1024-lane workgroups per CU, all resident (256: the same; 1024 x 512 lanes: slower)
 // (512-lane attention workgroups: in one run, same 512-workgroup grid, 256 -> 512 lanes took
 // c4 from 64.8 to 58.6 us and c2 from 16.1 to 13.5 us, c3 unchanged)
 #ifndef KVS_ATTN_THREADS

@@ -38,10 +38,28 @@
 
 namespace kvs {
 
+// Start and end time of every workgroup for the debugging harness (compiled only with
+// -DKVS_WG_TRACE_BUILD): two words per workgroup, in launch order.
+#ifdef KVS_WG_TRACE_BUILD
+static __device__ long long g_predict_wg_trace[2 * 8192];
+extern "C" int kvs_debug_predict_wg_trace(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_predict_wg_trace), sizeof(long long) * (size_t)n);
+}
+#define KVS_WG_TRACE(i)                                                                        \
+  do {                                                                                         \
+    const int wg_ = blockIdx.y * gridDim.x + blockIdx.x;                                       \
+    if (threadIdx.x == 0 && wg_ < 8192) g_predict_wg_trace[2 * wg_ + (i)] = wall_clock64();    \
+  } while (0)
+#else
+#define KVS_WG_TRACE(i)
+#endif
+
 template <typename E, int R, int G, bool HIST, bool PAD>
 __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictArgs a) {
   __shared__ PredictShared<E, R, G, HIST> sh;
-  predict_item<E, R, G, HIST, PAD, false>(sh, a, blockIdx.y, blockIdx.x);
+  KVS_WG_TRACE(0);
+  predict_item<E, R, G, HIST, PAD, false, kPredictUnroll, kPredictThreads, true>(sh, a, blockIdx.y, blockIdx.x);
+  KVS_WG_TRACE(1);
 }
 
 

@@ -21,10 +21,11 @@ constexpr int kPredictThreads = kPredictWgThreads;
 constexpr int kPredictWaves = kPredictThreads / kWave;
 constexpr int kPredictUnroll = kPredictUnitsPerWgStep / kPredictWaves;  // wave-loads in flight per wave
 static_assert(kPredictUnroll * kPredictWaves == kPredictUnitsPerWgStep, "granule mismatch");
+constexpr int kStepPredictThreads = 512;  // workgroup size of the single-launch step's prediction items
 
 // Geometry of one instantiation: E metadata element, R rank, G row slots per group, UNROLL
-// wave-wide loads a wave keeps in flight (4 in the prediction kernel, whose 54-62 registers
-// let four workgroups share a compute unit; more where fewer waves are resident).
+// wave-wide loads a wave keeps in flight (4 in the prediction kernel, whose 54-64 registers
+// let 32 waves share a compute unit; more where fewer waves are resident).
 template <typename E, int R, int G, int UNROLL = kPredictUnroll>
 struct PredictGeom {
   static constexpr int EPL = E::kPerLane;
@@ -40,13 +41,14 @@ struct PredictGeom {
 };
 
 // LDS of one prediction work item.
-template <typename E, int R, int G, bool HIST, int UNROLL = kPredictUnroll>
+template <typename E, int R, int G, bool HIST, int UNROLL = kPredictUnroll, int THREADS = kPredictThreads>
 struct PredictShared {
   float qsum[128];
-  float red[kPredictThreads];
+  float red[THREADS];
   float qlr[R];
   int hist[HIST ? kTopkBins : 1];
-  float stage[kPredictWaves][PredictGeom<E, R, G, UNROLL>::kGroupsPerBatch];  // group scores of a wave's batch
+  float stage[THREADS / kWave][PredictGeom<E, R, G, UNROLL>::kGroupsPerBatch];  // group scores of a wave's batch
+  int next_batch;  // WAVE_CLAIMS: the next batch of the workgroup's chunk that no wave has taken
 };
 
 // What a prediction launch is given (the same for all its work items).
@@ -68,9 +70,19 @@ struct PredictArgs {
 // group scores are written with device-scope stores, for a reader in another workgroup of
 // the same launch (otherwise plain stores, complete at the end of the kernel).  The routine
 // ends without a barrier: before its LDS is reused the caller needs one.
-template <typename E, int R, int G, bool HIST, bool PAD, bool PUBLISH, int UNROLL = kPredictUnroll>
-__device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL>& sh, const PredictArgs& a,
-                                             int p, int chunk) {
+//
+// WAVE_CLAIMS: the waves do not walk the chunk in lockstep order (wave w: batch w of every
+// workgroup step) but take its batches of U units one at a time from a counter in LDS, the
+// first one by wave index, each following one drawn while the current one's loads travel.
+// Why: a compute unit serves the loads of its older waves first, so with a fixed split some
+// waves finish long before others and the last ones stream alone; with claims all waves of a
+// workgroup end within one batch of each other.  Which wave computes which group score
+// depends on timing, the score does not.
+template <typename E, int R, int G, bool HIST, bool PAD, bool PUBLISH, int UNROLL = kPredictUnroll,
+          int THREADS = kPredictThreads, bool WAVE_CLAIMS = false>
+__device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL, THREADS>& sh,
+                                             const PredictArgs& a, int p, int chunk) {
+  constexpr int kPredictThreads = THREADS, kPredictWaves = THREADS / kWave;  // (of this instantiation)
   using Geom = PredictGeom<E, R, G, UNROLL>;
   constexpr int EPL = Geom::EPL, LPR = Geom::LPR, RPU = Geom::RPU, UPG = Geom::UPG, U = Geom::U;
   constexpr bool kGroupInUnit = Geom::kGroupInUnit;
@@ -111,7 +123,9 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
   // consecutive units starting at w * U, i.e. one contiguous run of U KiB, whose group
   // scores are U * RPU / G consecutive floats that leave in one coalesced store.
   constexpr int kStep = kPredictWaves * U;
-  auto unit_of = [&](int step_base, int j) { return step_base + wave * U + j; };
+  // (with WAVE_CLAIMS a base is that of the wave's own batch)
+  const int wave_off = WAVE_CLAIMS ? 0 : wave * U;
+  auto unit_of = [&](int step_base, int j) { return step_base + wave_off + j; };
   uint4 v[U];
   bool ok[U];
   auto issue = [&](int step_base) {
@@ -135,7 +149,11 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
   // Everything the prologue needs from memory is requested up front - the queries, this
   // lane's entries of the adapter, and the first batch of K_lr - so that the workgroup
   // pays one memory latency before it streams, not three in a row.
-  constexpr int NSL = kPredictThreads / R;  // slices of the d axis in the projection
+  // (the projection is done by the first 512 lanes whatever the workgroup size, so that its
+  // summation order, and with it every score, is the same in all launch forms)
+  constexpr int kProjectLanes = 512;
+  static_assert(kPredictThreads >= kProjectLanes, "the projection needs 512 lanes");
+  constexpr int NSL = kProjectLanes / R;    // slices of the d axis in the projection
   constexpr int kSpanMax = 128 / NSL;       // adapter rows per lane at d = 128
   const int pj = tid % R, psl = tid / R;
   const int span = d / NSL;
@@ -149,12 +167,17 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
     const float* Ak = A + (size_t)k * d * R;
 #pragma unroll
     for (int i = 0; i < kSpanMax; ++i)
-      a_reg[i] = Ak[(size_t)min(psl * span + i, d - 1) * R + pj];  // rows past the span are never used
+      a_reg[i] = psl < NSL ? Ak[(size_t)min(psl * span + i, d - 1) * R + pj] : 0.f;  // rows past the span are never used
   } else {
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qr[e] = qlr[(size_t)p * R + c * EPL + e] * meta_scale;
   }
-  int ub = u0;  // base of the current workgroup step
+  int ub = u0;  // base of the current workgroup step (WAVE_CLAIMS: of the wave's current batch)
+  int drawn = 0;  // WAVE_CLAIMS: the batch this wave takes next (valid in lane 0 until broadcast)
+  if constexpr (WAVE_CLAIMS) {
+    ub = u0 + wave * U;
+    if (tid == 0) sh.next_batch = kPredictWaves;  // (visible after the barriers of the prologue)
+  }
   if (ub < u1) issue(ub);
 
   if constexpr (HIST) {  // this workgroup's share of the score histogram
@@ -168,7 +191,7 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
     float acc = 0.f;
 #pragma unroll
     for (int i = 0; i < kSpanMax; ++i)
-      if (i < span) acc = fmaf(s_qsum[psl * span + i], a_reg[i], acc);
+      if (i < span && psl < NSL) acc = fmaf(s_qsum[psl * span + i], a_reg[i], acc);
     s_red[tid] = acc;
     lds_barrier();
     if (tid < R) {
@@ -181,8 +204,8 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
 #pragma unroll
     // the stored metadata is K.A / meta_scale: the factor goes into the query once
     for (int e = 0; e < EPL; ++e) qr[e] = s_qlr[c * EPL + e] * meta_scale;
-  } else if constexpr (HIST) {
-    lds_barrier();  // the histogram is cleared before anyone counts into it
+  } else if constexpr (HIST || WAVE_CLAIMS) {
+    lds_barrier();  // the histogram is cleared before anyone counts into it (and the batch counter set)
   }
 
   KVS_PREDICT_TRACE(1);
@@ -190,6 +213,9 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
   const float empty = mean ? 0.f : -__builtin_huge_valf();  // score of an empty row slot
 
   while (ub < u1) {
+    if constexpr (WAVE_CLAIMS) {  // draw the batch after this one while this one's loads travel
+      if (lane == 0) drawn = atomicAdd(&sh.next_batch, 1);
+    }
     float sc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -244,7 +270,8 @@ __device__ __forceinline__ void predict_item(PredictShared<E, R, G, HIST, UNROLL
         }
       }
     }
-    ub += kStep;
+    if constexpr (WAVE_CLAIMS) ub = u0 + __builtin_amdgcn_readfirstlane(drawn) * U;
+    else ub += kStep;
     if (ub < u1) issue(ub);
     KVS_PREDICT_TRACE(2);
   }
