@@ -45,6 +45,9 @@ static __device__ long long g_attn_wg_trace[2 * 8192];
 extern "C" int kvs_debug_attn_wg_trace(long long* host, int n) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_wg_trace), sizeof(long long) * (size_t)n);
 }
+extern "C" int kvs_debug_attn_wave_end(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_wave_end), sizeof(long long) * (size_t)n);
+}
 #define KVS_WG_TRACE(i)                                                                     \
   do {                                                                                      \
     const int wg_ = blockIdx.y * gridDim.x + blockIdx.x;                                    \

@@ -6,6 +6,11 @@
 
 #include "attn_merge.h"
 
+#ifdef KVS_WG_TRACE_BUILD
+// (debug builds) the time every wave leaves its tile loop
+static __device__ long long g_attn_wave_end[8192];
+#endif
+
 namespace kvs {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -271,6 +276,9 @@ __device__ __forceinline__ bool attn_mfma_item(AttnMfmaShared<QPK, SEL_CAP>& sh,
   }
 
   KVS_ATTN_TRACE(2);
+#ifdef KVS_WG_TRACE_BUILD
+  if (lane == 0) g_attn_wave_end[((blockIdx.y * gridDim.x + blockIdx.x) * kAttnWaves + wave) & 8191] = wall_clock64();
+#endif
   // ---- this wave's state of head c: add up the four slices' denominators ----------------
   l += xor_lane<16>(l);
   l += xor_lane<32>(l);
