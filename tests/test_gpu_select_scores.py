@@ -57,7 +57,7 @@ RNG = np.random.default_rng(20251127)
 
 
 @pytest.mark.parametrize("NG,M", [(8192, 820), (8192, 1), (8192, 8191), (8192, 8192), (4096, 410), (1000, 77),
-                                  (999, 500), (7, 3), (1, 1), (16384, 1638), (32768, 3277), (30001, 12345),
+                                  (999, 500), (7, 3), (1, 1), (16384, 1638), (32768, 3277), (30001, 12345), (8193, 820), (12001, 4000), (16385, 1638),
                                   (8193, 2000), (20000, 50)])
 def test_random_scores(NG, M):
     gs = (RNG.standard_normal((5, NG)) * 20.0).astype(np.float32)
