@@ -291,6 +291,25 @@ kvs_status kvs_decode_step_single_launch(const kvs_params* p, const void* q, con
                                          float* group_scores, void* out, void* workspace,
                                          size_t workspace_bytes, void* stream);
 
+/* Sec. 3.3 / 3.4 (the pipeline over layers: the groups of the next layer are predicted
+ * while this layer computes): the attention of one layer and the top-M selection for the
+ * NEXT layer in one launch.  The selection is latency-bound and the attention is the one
+ * kernel of a pipelined step it does not depend on, so the selection's workgroups ride along
+ * in the attention's grid.  Equivalent, bit for bit, to
+ *     kvs_sparse_decode_attn(p, q, K, V, idx, out, workspace, ...);
+ *     kvs_select_topk(p, next_group_scores, next_idx, workspace, ...);
+ * with the workspace contract of kvs_select_topk (the histograms that kvs_predict_scores left
+ * in this workspace for next_group_scores are consumed and zeroed).  A pipelined step of
+ * layer i is then two launches: kvs_predict_scores for layer i+1, then this call (attention
+ * of layer i with the idx this call produced one step earlier, selection of layer i+1).
+ * idx and next_idx must not overlap.  Both layers have the shape `p`.
+ * Covers bf16 K/V with d = 128, 3 to 8 query heads per KV head and at most 16384 groups per
+ * selection set (either head mode); KVS_ERR_UNSUPPORTED otherwise. */
+kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, void* out, const float* next_group_scores,
+                                  int32_t* next_idx, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 /* kvs_decode_step with the rolling buffer in the attention (kvs_predict_select, then
  * kvs_sparse_decode_attn_rb). */
 kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_lr,

@@ -25,7 +25,7 @@ EXPORTS = (
     "kvs_predict_scores", "kvs_select_topk",
     "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_sparse_decode_attn_paged",
     "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb", "kvs_decode_step_static",
-    "kvs_decode_step_single_launch",
+    "kvs_decode_step_single_launch", "kvs_attend_select_next",
     "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
@@ -156,6 +156,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_decode_step.restype = ctypes.c_int
     lib.kvs_decode_step_single_launch.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_decode_step_single_launch.restype = ctypes.c_int
+    lib.kvs_attend_select_next.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_attend_select_next.restype = ctypes.c_int
     lib.kvs_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kvs_decode_step_static.restype = ctypes.c_int
     lib.kvs_status_str.argtypes = [ctypes.c_int]
@@ -364,6 +366,16 @@ def kvs_sparse_decode_attn(p: Params, q, K, V, idx, out, workspace, stream=None)
     c = p._c()
     head, tail = _attn_args(p, q, K, V, idx, out, workspace, stream)
     _check(load_library().kvs_sparse_decode_attn(ctypes.byref(c), *head, *tail), "kvs_sparse_decode_attn")
+
+
+def kvs_attend_select_next(p: Params, q, K, V, idx, out, next_group_scores, next_idx, workspace, stream=None) -> None:
+    torch = _torch()
+    c = p._c()
+    head, tail = _attn_args(p, q, K, V, idx, out, workspace, stream)
+    nxt = [_dev(next_group_scores, torch.float32, p.sets + (p.n_groups,), "next_group_scores"),
+           _dev(next_idx, torch.int32, p.sets + (p.n_select,), "next_idx")]
+    _check(load_library().kvs_attend_select_next(ctypes.byref(c), *head, tail[0], *nxt, *tail[1:]),
+           "kvs_attend_select_next")
 
 
 def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, workspace, stream=None) -> None:

@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvswap_hip.so")
-SOURCES = ["api.hip", "predict.hip", "topk.hip", "attn.hip", "attn_mfma.hip", "build_metadata.hip", "fused.hip"]
+SOURCES = ["api.hip", "predict.hip", "topk.hip", "attn.hip", "attn_mfma.hip", "build_metadata.hip", "fused.hip", "attn_select.hip"]
 # Packed-fp32 VALU forms are switched off for all device code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",

@@ -141,6 +141,14 @@ hipError_t launch_overlap(const kvs_params& p, const Plan& pl, const int32_t* id
                           const int32_t* idx_cur, int32_t* common, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
+// The attention of one layer and the selection for the next in one launch (matrix-core
+// attention layouts, at most 16384 groups per set): whether it covers these parameters, and
+// its launch.  hist as in launch_topk.
+bool attn_select_applies(const kvs_params& p, const Plan& pl);
+hipError_t launch_attn_select(const kvs_params& p, const Plan& pl, const void* q, const void* K, const void* V,
+                              const int32_t* idx, float* part_ml, float* part_o, void* out, int* arrivals,
+                              const float* next_gs, int32_t* next_idx, int* hist, hipStream_t st);
+
 // The whole step (prediction, selection, attention) as one launch of a persistent grid:
 // whether it covers these parameters, and its launch.  gs: the workspace's score area (the
 // selection items read a little beyond its end, into the padding make_plan leaves there);
