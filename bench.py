@@ -126,26 +126,50 @@ class Workload:
             for l in range(self.layers_per_step):
                 self.layer_step(l)
 
+    def pipelined_in_two_launches(self) -> bool:
+        """Whether kvs_attend_select_next covers this workload's layout (bf16, d = 128, 3..8
+        query heads per KV head, at most 16384 groups per selection set)."""
+        c = self.cfg
+        return (c.dtype != "f32" and c.head_dim == 128 and 3 <= c.n_q_heads // c.n_kv_heads <= 8
+                and c.n_groups <= 16384)
+
     def run(self, count: int, layer_ahead: bool = False):
         """`count` steps on the current stream.  With `layer_ahead`, the layer-steps are
         issued the way the method's runtime pipelines them (Sec. 3.3, 3.4: the groups of
-        layer i are predicted while layer i-1 is still computing, from a query known one
-        layer early): prediction, selection and attention each on a stream of their own,
-        chained per layer by events, so the prediction of the following layers overlaps
-        the selection and attention of this one.  Forks from and joins the current stream,
-        so the whole thing can be captured into a graph."""
+        layer i+1 are predicted while layer i is still computing, from a query known one
+        layer early).  Where kvs_attend_select_next covers the layout that is two launches
+        per layer on ONE stream - the prediction of layer i+1, then the attention of layer i
+        together with the selection of layer i+1 - with the ordinary calls at both ends, so
+        that `count` steps still hold exactly `count` predictions, selections and
+        attentions.  Elsewhere (fp32, d = 64): prediction, selection and attention each on
+        a stream of their own, chained per layer by events, forked from and joined to the
+        current stream so that the whole thing can be captured into a graph."""
         if not layer_ahead:
             for i in range(count):
                 self.step(i)
             return
         torch, kv, p = self.torch, self.kv, self.p
+        n = count * self.layers_per_step
+        if self.pipelined_in_two_launches():
+            ws = self.ws
+            slot = lambda j: self.slots[j % len(self.slots)]
+            s = slot(0)
+            kv.kvs_predict_select(p, s["q"], s["K_lr"], s["A"], s["idx"], None, ws)
+            for j in range(n):
+                s = slot(j)
+                if j + 1 < n:
+                    t = slot(j + 1)
+                    kv.kvs_predict_scores(p, t["q"], t["K_lr"], t["A"], t["gs"], ws)
+                    kv.kvs_attend_select_next(p, s["q"], s["K"], s["V"], s["idx"], s["out"], t["gs"], t["idx"], ws)
+                else:
+                    kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], ws)
+            return
         main = torch.cuda.current_stream()
         if not hasattr(self, "side"):
             self.side = (torch.cuda.Stream(), torch.cuda.Stream())
         s_sel, s_att = self.side
         s_sel.wait_stream(main)
         s_att.wait_stream(main)
-        n = count * self.layers_per_step
         last = {}                                       # slot -> event of its last attention
         for j in range(n):
             k = j % len(self.slots)
@@ -179,7 +203,9 @@ def time_steps(wl: Workload, steps: int, warmup: int, mode: str, layer_ahead: bo
     # launch of the graph itself stays a small part of a replay
     # (layer-ahead: exactly one rotation, so that no copy - standing in for a layer - is used
     # twice inside a graph and has to wait for its own previous use)
-    n = 1 if wl.layers_per_step != 1 else len(wl.slots) * (1 if layer_ahead else max(1, -(-24 // len(wl.slots))))
+    # (the two-launch pipelined form runs on one stream and may reuse a copy like the serial form)
+    one_rotation = layer_ahead and not wl.pipelined_in_two_launches()
+    n = 1 if wl.layers_per_step != 1 else len(wl.slots) * (1 if one_rotation else max(1, -(-24 // len(wl.slots))))
     out = []
     if mode == "eager":
         wl.run(warmup, layer_ahead)
@@ -425,7 +451,11 @@ def measure(cfg, steps, warmup, mode, copies=None, log=print, want_cpu=True, met
             "step_hbm_frac": ab["step"] * layers / (single_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "layer_ahead": None if ahead_ms is None else {
             "us_per_layer": ahead_ms * 1e3 / layers,
-            "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+            "step_hbm_frac": ab["step"] * layers / (ahead_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "form": ("two launches per layer on one stream: kvs_predict_scores of layer i+1, then "
+                     "kvs_attend_select_next (attention of layer i with the selection of layer i+1)"
+                     if wl.pipelined_in_two_launches() else
+                     "prediction, selection and attention on three streams chained by events")},
     }
     if want_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, wl.host0, budget_s=cpu_budget_s, meta=meta)
