@@ -240,3 +240,25 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit_before_any_launch(
     text = open(HEADER).read()
     assert re.search(r"#define\s+KVS_STATIC_SCRATCH_BYTES\s+\(8u\s*<<\s*20\)", text)
     assert kv.KVS_STATIC_SCRATCH_BYTES == 8 << 20
+
+
+def test_pipelined_entry_point_checks_its_arguments_on_the_host():
+    """kvs_attend_select_next: NULL pointers, misaligned buffers, a missing or short
+    workspace and layouts outside its set are refused before any launch (fake addresses)."""
+    lib = kv.load_library()
+    fake, odd, null = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x10004), ctypes.c_void_p(0)
+    big = 1 << 30
+    f = lambda p, *a: lib.kvs_attend_select_next(ctypes.byref(p._c()), *a)
+    ok = _p()          # bf16, d = 128, four query heads per KV head
+    assert f(ok, fake, fake, fake, fake, fake, null, fake, fake, big, null) == E_NULL      # no scores
+    assert f(ok, fake, fake, fake, fake, fake, fake, null, fake, big, null) == E_NULL      # no next_idx
+    assert f(ok, fake, fake, fake, null, fake, fake, fake, fake, big, null) == E_NULL      # no idx
+    assert f(ok, fake, fake, fake, fake, fake, odd, fake, fake, big, null) == E_ALIGN
+    assert f(ok, fake, fake, fake, fake, fake, fake, fake, null, big, null) == E_WS
+    assert f(ok, fake, fake, fake, fake, fake, fake, fake, fake, 64, null) == E_WS
+    fp32 = _p(kv_dtype=kv.KVS_F32, meta_dtype=kv.KVS_F32, head_dim=64)
+    assert f(fp32, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP
+    two_heads = _p(n_q_heads=16, n_kv_heads=8)
+    assert f(two_heads, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP
+    long_ctx = _p(ctx_len=131072, n_select=1638)      # 32768 groups: beyond one 512-lane workgroup's keys
+    assert f(long_ctx, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP
