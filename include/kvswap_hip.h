@@ -310,6 +310,15 @@ kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void
                                   int32_t* next_idx, void* workspace, size_t workspace_bytes,
                                   void* stream);
 
+/* The same with the rolling buffer in the attention (Sec. 3.4.1; arguments and limits as in
+ * kvs_sparse_decode_attn_rb): equivalent, bit for bit, to kvs_sparse_decode_attn_rb followed
+ * by kvs_select_topk.  rb_len = 0 is kvs_attend_select_next. */
+kvs_status kvs_attend_select_next_rb(const kvs_params* p, const void* q, const void* K, const void* V,
+                                     const int32_t* idx, const void* rb_K, const void* rb_V,
+                                     int32_t rb_len, int32_t rb_capacity, void* out,
+                                     const float* next_group_scores, int32_t* next_idx, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
 /* kvs_decode_step with the rolling buffer in the attention (kvs_predict_select, then
  * kvs_sparse_decode_attn_rb). */
 kvs_status kvs_decode_step_rb(const kvs_params* p, const void* q, const void* K_lr,

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     kvs_build_metadata, kvs_build_metadata_rows, kvs_append_group,
     kvs_predict_select, kvs_predict_scores, kvs_select_topk,
     kvs_sparse_decode_attn, kvs_sparse_decode_attn_rb, kvs_sparse_decode_attn_paged,
-    kvs_selection_overlap, kvs_decode_step, kvs_decode_step_rb, kvs_decode_step_static, kvs_decode_step_single_launch, kvs_attend_select_next,
+    kvs_selection_overlap, kvs_decode_step, kvs_decode_step_rb, kvs_decode_step_static, kvs_decode_step_single_launch, kvs_attend_select_next, kvs_attend_select_next_rb,
     KVS_STATIC_SCRATCH_BYTES,
 )

@@ -25,7 +25,7 @@ EXPORTS = (
     "kvs_predict_scores", "kvs_select_topk",
     "kvs_sparse_decode_attn", "kvs_sparse_decode_attn_rb", "kvs_sparse_decode_attn_paged",
     "kvs_selection_overlap", "kvs_decode_step", "kvs_decode_step_rb", "kvs_decode_step_static",
-    "kvs_decode_step_single_launch", "kvs_attend_select_next",
+    "kvs_decode_step_single_launch", "kvs_attend_select_next", "kvs_attend_select_next_rb",
     "kvs_status_str", "kvs_version", "kvs_last_device_error",
 )
 
@@ -158,6 +158,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvs_decode_step_single_launch.restype = ctypes.c_int
     lib.kvs_attend_select_next.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_attend_select_next.restype = ctypes.c_int
+    lib.kvs_attend_select_next_rb.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvs_attend_select_next_rb.restype = ctypes.c_int
     lib.kvs_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kvs_decode_step_static.restype = ctypes.c_int
     lib.kvs_status_str.argtypes = [ctypes.c_int]
@@ -376,6 +378,17 @@ def kvs_attend_select_next(p: Params, q, K, V, idx, out, next_group_scores, next
            _dev(next_idx, torch.int32, p.sets + (p.n_select,), "next_idx")]
     _check(load_library().kvs_attend_select_next(ctypes.byref(c), *head, tail[0], *nxt, *tail[1:]),
            "kvs_attend_select_next")
+
+
+def kvs_attend_select_next_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, next_group_scores, next_idx,
+                              workspace, stream=None) -> None:
+    torch = _torch()
+    c = p._c()
+    head, tail = _attn_args(p, q, K, V, idx, out, workspace, stream)
+    nxt = [_dev(next_group_scores, torch.float32, p.sets + (p.n_groups,), "next_group_scores"),
+           _dev(next_idx, torch.int32, p.sets + (p.n_select,), "next_idx")]
+    _check(load_library().kvs_attend_select_next_rb(ctypes.byref(c), *head, *_rb(p, rb_K, rb_V, rb_len), tail[0],
+                                                    *nxt, *tail[1:]), "kvs_attend_select_next_rb")
 
 
 def kvs_sparse_decode_attn_rb(p: Params, q, K, V, idx, rb_K, rb_V, rb_len, out, workspace, stream=None) -> None:

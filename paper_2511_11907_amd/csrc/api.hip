@@ -346,13 +346,16 @@ kvs_status attend(const kvs_params* p, const void* q, const void* K, const void*
 }
 }  // namespace
 
-kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void* K, const void* V,
-                                  const int32_t* idx, void* out, const float* next_group_scores,
-                                  int32_t* next_idx, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+kvs_status kvs_attend_select_next_rb(const kvs_params* p, const void* q, const void* K, const void* V,
+                                     const int32_t* idx, const void* rb_K, const void* rb_V,
+                                     int32_t rb_len, int32_t rb_capacity, void* out,
+                                     const float* next_group_scores, int32_t* next_idx, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
   if (!p || !q || !K || !V || !idx || !out || !next_group_scores || !next_idx) return KVS_ERR_NULL;
   kvs_status s = check_params(p, true);
   if (s != KVS_OK) return s;
+  RollingBuffer rb;
+  if ((s = check_rb(rb_K, rb_V, rb_len, rb_capacity, &rb)) != KVS_OK) return s;
   if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(out) ||
       misaligned(next_group_scores) || misaligned(next_idx))
     return KVS_ERR_ALIGN;
@@ -362,8 +365,16 @@ kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void
   float* part_ml = (float*)((char*)workspace + pl.off_part_ml);
   float* part_o = (float*)((char*)workspace + pl.off_part_o);
   int* arrivals = (int*)((char*)workspace + pl.off_sync) + pl.sync_arrivals;
-  return dev(launch_attn_select(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, next_group_scores,
+  return dev(launch_attn_select(*p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, next_group_scores,
                                 next_idx, hist_handed_over(pl, workspace), (hipStream_t)stream));
+}
+
+kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void* K, const void* V,
+                                  const int32_t* idx, void* out, const float* next_group_scores,
+                                  int32_t* next_idx, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  return kvs_attend_select_next_rb(p, q, K, V, idx, nullptr, nullptr, 0, 0, out, next_group_scores, next_idx,
+                                   workspace, workspace_bytes, stream);
 }
 
 kvs_status kvs_sparse_decode_attn_rb(const kvs_params* p, const void* q, const void* K,

@@ -16,6 +16,8 @@
 #include "attn_mfma_item.h"
 #include "topk_block.h"
 
+#include <type_traits>
+
 namespace kvs {
 
 constexpr int kAttnSelectThreads = 512;
@@ -29,7 +31,8 @@ struct SelectNextArgs {
   int sets, NG, M;
 };
 
-template <int QPK, bool INTERLEAVE, int SLOTS>
+// MODE: kAttnPlain or kAttnRolling (the attention also covers the rolling buffer's tokens).
+template <int QPK, int MODE, bool INTERLEAVE, int SLOTS>
 __global__ __launch_bounds__(kAttnSelectThreads, 4) void attn_select_kernel(AttnMfmaArgs a, SelectNextArgs s) {
   union Shared {
     AttnMfmaShared<QPK, 0> attn;
@@ -43,7 +46,7 @@ __global__ __launch_bounds__(kAttnSelectThreads, 4) void attn_select_kernel(Attn
     return;
   }
   const int item = wg - s.sets;
-  attn_mfma_item<QPK, kAttnPlain, INTERLEAVE, 0>(sh.attn, a, item / a.n_splits, item % a.n_splits);
+  attn_mfma_item<QPK, MODE, INTERLEAVE, 0>(sh.attn, a, item / a.n_splits, item % a.n_splits);
 }
 
 namespace {
@@ -51,7 +54,8 @@ namespace {
 template <int QPK>
 hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const void* K, const void* V,
                       const int32_t* idx, float* part_ml, float* part_o, void* out, int* arrivals,
-                      const float* next_gs, int32_t* next_idx, int* hist, hipStream_t st) {
+                      const RollingBuffer& rb, const float* next_gs, int32_t* next_idx, int* hist,
+                      hipStream_t st) {
   using S = uint16_t;
   const int G = p.group_size;
   int log2G = 0;
@@ -60,21 +64,31 @@ hipError_t launch_qpk(const kvs_params& p, const Plan& pl, const void* q, const 
   const uint32_t recipG = (uint32_t)((1ull << 32) / (unsigned)G + 1);  // (only read when log2G < 0)
   const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   // the split plan of the stand-alone attention kernel
-  const int units = pl.attn_units, units_per_split = attn_units_per_split_with_buffer(pl, pl.attn_units);
+  const int units = (p.n_select * p.group_size + rb.len + pl.kv_toks_per_unit - 1) / pl.kv_toks_per_unit;
+  const int units_per_split = attn_units_per_split_with_buffer(pl, units);
   const bool interleave = units_per_split >= kAttnInterleaveFromSteps * kAttnUnitsPerWgStep;
   const AttnMfmaArgs a{(const S*)q, (const S*)K, (const S*)V, idx, part_ml, part_o, (S*)out, arrivals,
                        p.n_kv_heads, pl.kv_heads_per_set, pl.ctx_rows, p.n_select, G, log2G, recipG, units,
-                       units_per_split, pl.attn_splits, scale * kLog2e, nullptr, nullptr, 0, 0, nullptr,
-                       pl.n_groups};
+                       units_per_split, pl.attn_splits, scale * kLog2e, (const S*)rb.K, (const S*)rb.V, rb.len,
+                       rb.capacity, nullptr, pl.n_groups};
   const SelectNextArgs s{next_gs, next_idx, hist, pl.sets, pl.n_groups, p.n_select};
   const dim3 grid(pl.sets + pl.problems * pl.attn_splits), block(kAttnSelectThreads);
   const bool small = pl.n_groups <= kAttnSelectThreads * 16;
-  if (interleave) {
-    if (small) hipLaunchKernelGGL((attn_select_kernel<QPK, true, 16>), grid, block, 0, st, a, s);
-    else hipLaunchKernelGGL((attn_select_kernel<QPK, true, kTopkMaxPerLane>), grid, block, 0, st, a, s);
+  auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, st, a, s); };
+  auto pick = [&](auto mode, auto il) {
+    constexpr int M_ = decltype(mode)::value;
+    constexpr bool I_ = decltype(il)::value;
+    if (small) launch(attn_select_kernel<QPK, M_, I_, 16>);
+    else launch(attn_select_kernel<QPK, M_, I_, kTopkMaxPerLane>);
+  };
+  using Plain = std::integral_constant<int, kAttnPlain>;
+  using Rolling = std::integral_constant<int, kAttnRolling>;
+  if (rb.len > 0) {
+    if (interleave) pick(Rolling{}, std::true_type{});
+    else pick(Rolling{}, std::false_type{});
   } else {
-    if (small) hipLaunchKernelGGL((attn_select_kernel<QPK, false, 16>), grid, block, 0, st, a, s);
-    else hipLaunchKernelGGL((attn_select_kernel<QPK, false, kTopkMaxPerLane>), grid, block, 0, st, a, s);
+    if (interleave) pick(Plain{}, std::true_type{});
+    else pick(Plain{}, std::false_type{});
   }
   return hipGetLastError();
 }
@@ -87,9 +101,10 @@ bool attn_select_applies(const kvs_params& p, const Plan& pl) {
 
 hipError_t launch_attn_select(const kvs_params& p, const Plan& pl, const void* q, const void* K, const void* V,
                               const int32_t* idx, float* part_ml, float* part_o, void* out, int* arrivals,
-                              const float* next_gs, int32_t* next_idx, int* hist, hipStream_t st) {
+                              const RollingBuffer& rb, const float* next_gs, int32_t* next_idx, int* hist,
+                              hipStream_t st) {
 #define KVS_CASE(n) \
-  case n: return launch_qpk<n>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, next_gs, next_idx, hist, st);
+  case n: return launch_qpk<n>(p, pl, q, K, V, idx, part_ml, part_o, out, arrivals, rb, next_gs, next_idx, hist, st);
   switch (pl.q_per_kv) {
     KVS_CASE(3) KVS_CASE(4) KVS_CASE(5) KVS_CASE(6) KVS_CASE(7) KVS_CASE(8)
   }

@@ -147,7 +147,8 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 bool attn_select_applies(const kvs_params& p, const Plan& pl);
 hipError_t launch_attn_select(const kvs_params& p, const Plan& pl, const void* q, const void* K, const void* V,
                               const int32_t* idx, float* part_ml, float* part_o, void* out, int* arrivals,
-                              const float* next_gs, int32_t* next_idx, int* hist, hipStream_t st);
+                              const RollingBuffer& rb, const float* next_gs, int32_t* next_idx, int* hist,
+                              hipStream_t st);
 
 // The whole step (prediction, selection, attention) as one launch of a persistent grid:
 // whether it covers these parameters, and its launch.  gs: the workspace's score area (the

@@ -260,5 +260,9 @@ def test_pipelined_entry_point_checks_its_arguments_on_the_host():
     assert f(fp32, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP
     two_heads = _p(n_q_heads=16, n_kv_heads=8)
     assert f(two_heads, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP
+    g = lambda p, *a: lib.kvs_attend_select_next_rb(ctypes.byref(p._c()), *a)
+    assert g(ok, fake, fake, fake, fake, null, null, 3, 8, fake, fake, fake, fake, big, null) == E_NULL   # rb_len without a buffer
+    assert g(ok, fake, fake, fake, fake, fake, fake, 9, 8, fake, fake, fake, fake, big, null) == E_SHAPE  # rb_len > capacity
+    assert g(ok, fake, fake, fake, fake, fake, fake, 3, 8, fake, fake, fake, null, big, null) == E_WS
     long_ctx = _p(ctx_len=131072, n_select=1638)      # 32768 groups: beyond one 512-lane workgroup's keys
     assert f(long_ctx, fake, fake, fake, fake, fake, fake, fake, fake, big, null) == E_UNSUP

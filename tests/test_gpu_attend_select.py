@@ -165,3 +165,44 @@ def test_layouts_outside_its_set_are_refused():
     st = lib.kvs_attend_select_next(ctypes.byref(p._c()), a, a, a, a, a, None, a,
                                     ctypes.c_void_p(ws.data_ptr()), ws.numel() * 4, None)
     assert st == 1     # KVS_ERR_NULL
+
+
+@pytest.mark.parametrize("cfg,cap", [(_c2(ctx_len=8192, n_select=205), 4), (_c4(), 8),
+                                     (_c4(batch=2, ctx_len=65536, n_select=2048), 8),
+                                     (PRESETS["c2j"].replace(name="c2ja", batch=2, ctx_len=4096, n_select=103), 4)],
+                         ids=["r32_G4", "r64_G8", "r64_G8_interleaved", "joint"])
+def test_with_the_rolling_buffer_it_equals_the_rolling_buffer_attention_and_the_selection(cfg, cap):
+    """kvs_attend_select_next_rb for every fill of the buffer: outputs equal
+    kvs_sparse_decode_attn_rb's and the next layer's indices kvs_select_topk's, bit for bit;
+    with an empty buffer it is kvs_attend_select_next."""
+    cur = Layer(cfg)
+    nxt = Layer(cfg, seq_offset=1, adapter_from=cur.L.A)
+    p = H.kv_params(cfg)
+    ws = H.workspace(p)
+    rng = np.random.default_rng(5)
+    shape = (cfg.batch, cfg.n_kv_heads, cap, cfg.head_dim)
+    rbK = (rng.standard_normal(shape) * 0.7).astype(np.float32)
+    rbV = rng.standard_normal(shape).astype(np.float32)
+    drK = torch.from_numpy(rbK).to(H.DEV).to(cur.D.K.dtype)
+    drV = torch.from_numpy(rbV).to(H.DEV).to(cur.D.K.dtype)
+    idx, _, _ = _bufs(cfg, p, cur.D.q)
+    kv.kvs_predict_select(p, cur.D.q, cur.klr_dev, cur.D.A, idx, None, ws)
+    idx_ref, gs_next, _ = _bufs(cfg, p, cur.D.q)
+    kv.kvs_predict_scores(p, nxt.D.q, nxt.klr_dev, nxt.D.A, gs_next, ws)
+    kv.kvs_select_topk(p, gs_next, idx_ref, ws)
+    for rb_len in sorted({0, 1, cap - 1, cap}):
+        _, _, out_ref = _bufs(cfg, p, cur.D.q)
+        kv.kvs_sparse_decode_attn_rb(p, cur.D.q, cur.D.K, cur.D.V, idx, drK, drV, rb_len, out_ref, ws)
+        idx_new, gs2, out = _bufs(cfg, p, cur.D.q)
+        kv.kvs_predict_scores(p, nxt.D.q, nxt.klr_dev, nxt.D.A, gs2, ws)
+        kv.kvs_attend_select_next_rb(p, cur.D.q, cur.D.K, cur.D.V, idx, drK, drV, rb_len, out, gs2, idx_new, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(idx_new, idx_ref), f"rb_len={rb_len}: selection"
+        assert torch.equal(_bits(out), _bits(out_ref)), f"rb_len={rb_len}: output"
+        if rb_len == 0:
+            _, _, out0 = _bufs(cfg, p, cur.D.q)
+            idx0 = torch.full_like(idx_new, -1)
+            kv.kvs_attend_select_next(p, cur.D.q, cur.D.K, cur.D.V, idx, out0, gs_next, idx0, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(idx0, idx_ref) and torch.equal(_bits(out0), _bits(out_ref))
+    assert not torch.isnan(out.float()).any()
