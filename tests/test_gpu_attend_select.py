@@ -206,3 +206,30 @@ def test_with_the_rolling_buffer_it_equals_the_rolling_buffer_attention_and_the_
             torch.cuda.synchronize()
             assert torch.equal(idx0, idx_ref) and torch.equal(_bits(out0), _bits(out_ref))
     assert not torch.isnan(out.float()).any()
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_at_the_benchmark_sizes_it_equals_the_separate_calls(name):
+    """The launch configuration bench.py times (c3: 64 problems of 8192 groups, unsplit
+    interleaving off; c4: 32 problems of 16384 groups, interleaved splits): outputs and the
+    selection equal the separate kernels' bit for bit.  (The separate kernels are compared
+    with the oracle at these sizes in test_gpu_parity.py; one layer's inputs serve as both
+    the attended and the next layer here.)"""
+    cfg = PRESETS[name]
+    L = make_layer(cfg, workers=16)
+    D = H.DeviceLayer(L)
+    p = H.kv_params(cfg)
+    ws = H.workspace(p)
+    klr = torch.empty(p.sets + (cfg.ctx_len, cfg.rank), dtype=torch.bfloat16, device=H.DEV)
+    kv.kvs_build_metadata(p, D.K, D.A, klr)
+    idx, gs, out_ref = _bufs(cfg, p, D.q)
+    kv.kvs_predict_select(p, D.q, klr, D.A, idx, gs, ws)
+    kv.kvs_sparse_decode_attn(p, D.q, D.K, D.V, idx, out_ref, ws)
+    idx_new, gs2, out = _bufs(cfg, p, D.q)
+    kv.kvs_predict_scores(p, D.q, klr, D.A, gs2, ws)
+    kv.kvs_attend_select_next(p, D.q, D.K, D.V, idx, out, gs2, idx_new, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gs2, gs)
+    assert torch.equal(idx_new, idx), "selection"
+    assert torch.equal(_bits(out), _bits(out_ref)), "output"
+    assert int((idx_new[..., 1:] <= idx_new[..., :-1]).sum()) == 0      # ascending, distinct
