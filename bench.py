@@ -159,7 +159,10 @@ class Workload:
                 s = slot(j)
                 if j + 1 < n:
                     t = slot(j + 1)
-                    kv.kvs_predict_scores(p, t["q"], t["K_lr"], t["A"], t["gs"], ws)
+                    # (no workspace, i.e. no score histogram handed to the selection: hidden behind
+                    # the attention the selection gains nothing from it, and the prediction kernel
+                    # saves the atomics; joint-head mode keeps its low-rank queries there)
+                    kv.kvs_predict_scores(p, t["q"], t["K_lr"], t["A"], t["gs"], ws if self.cfg.joint else None)
                     kv.kvs_attend_select_next(p, s["q"], s["K"], s["V"], s["idx"], s["out"], t["gs"], t["idx"], ws)
                 else:
                     kv.kvs_sparse_decode_attn(p, s["q"], s["K"], s["V"], s["idx"], s["out"], ws)

@@ -302,7 +302,10 @@ kvs_status kvs_decode_step_single_launch(const kvs_params* p, const void* q, con
  * in this workspace for next_group_scores are consumed and zeroed).  A pipelined step of
  * layer i is then two launches: kvs_predict_scores for layer i+1, then this call (attention
  * of layer i with the idx this call produced one step earlier, selection of layer i+1).
- * idx and next_idx must not overlap.  Both layers have the shape `p`.
+ * idx and next_idx must not overlap.  Both layers have the shape `p`.  Hidden behind the
+ * attention, the selection gains nothing from the histogram hand-over, which costs the
+ * prediction kernel about a microsecond: in this form kvs_predict_scores is best called
+ * without a workspace (per-head mode), and the selection builds its own histogram.
  * Covers bf16 K/V with d = 128, 3 to 8 query heads per KV head and at most 16384 groups per
  * selection set (either head mode); KVS_ERR_UNSUPPORTED otherwise. */
 kvs_status kvs_attend_select_next(const kvs_params* p, const void* q, const void* K, const void* V,
